@@ -1,0 +1,152 @@
+"""Benchmark of the TLQ scale-search hot path on one MI355X.
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W]
+
+A step is one pass of the whole hot path (x_stat, scale table, fake
+quantisation of every candidate, fused contraction + weighted loss, final
+combine and selection) over the seven linears of one 7B-class decoder layer
+with 16 x 640 synthetic calibration tokens and a 20-point alpha grid:
+7 x 20 = 140 candidate evaluations.  Inputs (X, W, Y_ref, token weights) are
+resident in HBM before the timed region.  Prints ONE JSON line.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+METRIC = "candidate-scale evals/sec per layer + fused-kernel TFLOP/s (% fp16 MFMA peak)"
+PEAK_FP16_TFLOPS = 2500.0      # MI355X dense fp16 MFMA peak (published)
+# HBM bytes per gemm_loss launch measured with rocprofv3 --pmc (FETCH_SIZE + WRITE_SIZE,
+# scaled by a copy kernel of known size); None until a counter run has been committed
+# under profiles/.
+MEASURED_TRAFFIC_BYTES_PER_LAUNCH = None
+
+
+def cpu_baseline(wl, orc, workload):
+    """Time the oracle, as it stands, on a bounded sample of the same workload:
+    the q_proj-shaped linear, the first 4 calibration samples (2560 of 10240
+    tokens), 4 of the 20 candidates.  Reported as full-size evaluations per
+    second (the oracle's cost is linear in the token count)."""
+    import numpy as np
+    try:
+        from threadpoolctl import threadpool_info
+        cores = max([i.get("num_threads", 1) for i in threadpool_info()] or [os.cpu_count() or 1])
+    except Exception:
+        cores = os.cpu_count() or 1
+    n_samp, cand = 4, [0, 5, 10, 15]
+    X = wl.make_tokens(workload, 0, samples=range(n_samp))
+    W = wl.make_weight(workload, 0)
+    w = wl.make_token_weights(workload, 0)[: X.shape[0]]
+    al = wl.alpha_grid(workload.n_alpha)[cand]
+    Y = orc.ref_output(X, W).astype(np.float16)
+    t0 = time.perf_counter()
+    orc.scale_search(X, W, Y, w, workload.bits, workload.group, al)
+    dt = time.perf_counter() - t0
+    frac = X.shape[0] / workload.n_tok
+    return {"value": len(cand) / dt * frac, "unit": "evals/s", "cores": int(cores), "kind": "oracle",
+            "sample": f"{workload.name} q_proj 4096x4096, {X.shape[0]} of {workload.n_tok} tokens, "
+                      f"{len(cand)} of {workload.n_alpha} candidates, {dt:.1f} s of numpy fp64; "
+                      "scaled linearly in tokens to full-size evaluations"}
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=5)
+    ap.add_argument("--warmup", type=int, default=2)
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on exactly one GPU (no sharding, no collectives); "
+              "run with --gpus 1", file=sys.stderr)
+        sys.exit(2)
+
+    import numpy as np
+    import torch
+
+    from paper_2602_07899_amd import tlq
+    from paper_2602_07899_amd import workloads as wl
+
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible", file=sys.stderr)
+        sys.exit(2)
+    dev = torch.device("cuda:0")
+    workload = wl.CONFIGS["cfg2_7b_w4"]
+    p = tlq.params(bits=workload.bits, group=workload.group, x_dtype=tlq.F16, yref_dtype=tlq.F16)
+    al = torch.from_numpy(wl.alpha_grid(workload.n_alpha)).to(dev)
+
+    # ---- inputs resident in HBM (Y_ref = f_fp output through the library's own GEMM)
+    layers = []
+    ws_bytes = 0
+    for li, spec in enumerate(workload.linears):
+        X = torch.from_numpy(wl.make_tokens(workload, li)).to(dev)
+        W = torch.from_numpy(wl.make_weight(workload, li)).to(dev)
+        w = torch.from_numpy(wl.make_token_weights(workload, li)).to(dev)
+        Y = torch.empty((workload.n_tok, spec.c_out), dtype=torch.float16, device=dev)
+        tlq.ref_output(X, W, Y, p)
+        out = (torch.empty(spec.c_in, dtype=torch.float32, device=dev),
+               torch.empty(1, dtype=torch.int32, device=dev),
+               torch.empty(workload.n_alpha, dtype=torch.float32, device=dev))
+        layers.append((spec, X, W, Y, w, out))
+        ws_bytes = max(ws_bytes, tlq.scale_search_workspace_bytes(workload.n_tok, spec.c_in, spec.c_out,
+                                                                  workload.n_alpha, p))
+    workspace = torch.empty(ws_bytes, dtype=torch.uint8, device=dev)
+    torch.cuda.synchronize()
+
+    def step():
+        for spec, X, W, Y, w, (best, idx, losses) in layers:
+            tlq.scale_search(X, W, Y, w, al, p, best, idx, losses, workspace=workspace)
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    tlq.profile_reset()
+    tlq.profile_enable(True)          # HIP events around every kernel, on the launch stream
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        step()
+    torch.cuda.synchronize()
+    dt = time.perf_counter() - t0
+    tlq.profile_enable(False)
+    kernels = {k.name: k for k in tlq.profile_read()}
+
+    evals = len(layers) * workload.n_alpha * args.steps
+    g = kernels["gemm_loss"]
+    tflops = g.total_work / (g.total_ms * 1e-3) / 1e12
+    flops_per_launch = g.total_work / g.launches
+    best_idx = [int(l[5][1].item()) for l in layers]
+
+    result = {
+        "metric": METRIC, "value": evals / dt, "unit": "evals/s", "n_gpus": 1,
+        "steps": args.steps, "warmup": args.warmup, "ms_per_step": dt / args.steps * 1e3,
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "f16",
+        "data": "synthetic",
+        "config": {"workload": workload.name, "linears": [f"{s.name}:{s.c_out}x{s.c_in}" for s in workload.linears],
+                   "n_tok": workload.n_tok, "bits": workload.bits, "group": workload.group,
+                   "n_alpha": workload.n_alpha, "evals_per_step": len(layers) * workload.n_alpha},
+        "fused_kernel_tflops": tflops, "pct_fp16_mfma_peak": 100.0 * tflops / PEAK_FP16_TFLOPS,
+        "roofline": {"bound": "mfma", "kernel": "gemm_loss", "achieved": tflops, "peak": PEAK_FP16_TFLOPS,
+                     "unit": "TFLOP/s", "frac": tflops / PEAK_FP16_TFLOPS,
+                     "avg_launch_ms": g.total_ms / g.launches, "flops_per_launch": flops_per_launch,
+                     "traffic": MEASURED_TRAFFIC_BYTES_PER_LAUNCH},
+        "kernels": {k.name: {"launches": k.launches, "ms": round(k.total_ms, 4),
+                             "rate": (k.total_work / (k.total_ms * 1e-3) / 1e9) if k.total_ms > 0 else None,
+                             "rate_unit": "GFLOP/s" if k.name.startswith("gemm") else "GB/s"}
+                    for k in kernels.values()},
+        "best_alpha_index": best_idx,
+    }
+    if not args.no_cpu_baseline:
+        from oracle import tlq_oracle as orc
+        result["cpu_baseline"] = cpu_baseline(wl, orc, workload)
+    print(json.dumps(result))
+
+
+if __name__ == "__main__":
+    main()

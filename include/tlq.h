@@ -1,0 +1,175 @@
+/*
+ * tlq.h - C ABI of libtlq: the data-parallel hot path of TLQ's layer-wise
+ * scale search on one AMD MI355X (gfx950).
+ *
+ * What the library computes (paper: "Rethinking Practical and Efficient
+ * Quantization Calibration for Vision-Language Models"):
+ *   for one linear layer with weights W [c_out, c_in] and calibration tokens
+ *   X [n_tok, c_in], and for every candidate exponent alpha_k of a grid,
+ *     s_k      = x_stat ^ alpha_k                        (Sec. 3.1.2, scale eq.)
+ *     Wq_k     = Q_w(W * diag(s_k))                       (Sec. 3.2.1, f_q)
+ *     Yq_k     = (X * diag(s_k)^-1) * Wq_k^T              (Sec. 2.2, smoothing eq.)
+ *     L_k      = sum_t w_t * (1/c_out) * sum_o (Y_ref[t,o] - Yq_k[t,o])^2
+ *                                                         (Sec. 3.2.1, objective)
+ *   and returns k* = argmin_k L_k together with s_{k*}.  Q_w is round-to-
+ *   nearest integer quantisation (Sec. 2.2) on a min/max grid per group of
+ *   consecutive input channels; activations stay in 16-bit floating point.
+ *
+ * Conventions that hold for every entry point
+ *   - Every data pointer is a DEVICE pointer owned by the caller.  The
+ *     library never allocates, frees or keeps device memory; scratch comes
+ *     from the caller's `workspace` (size from the matching *_workspace_bytes
+ *     query; 256-byte aligned).  A workspace that is too small gives
+ *     TLQ_ERR_WORKSPACE and nothing is launched.
+ *   - `stream` is the caller's hipStream_t passed as void* (NULL = the null
+ *     stream).  All work is enqueued on it in order; no entry point
+ *     synchronises with the host or copies to the host.  Outputs are device
+ *     resident and valid once the stream reaches the end of the call.
+ *   - The return value reports argument validation and launch errors only.
+ *     On any status other than TLQ_OK nothing was written.
+ *   - Matrices are row-major with a row stride (`ld*`) in ELEMENTS.  16-bit
+ *     matrices need 16-byte aligned base pointers and strides that are
+ *     multiples of 8; otherwise TLQ_ERR_ALIGN.  c_in must be a multiple of 8
+ *     and of `group` (TLQ_ERR_SHAPE otherwise).
+ *   - Calls on different streams may run concurrently if their workspaces and
+ *     outputs are disjoint.
+ */
+#ifndef TLQ_H
+#define TLQ_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define TLQ_VERSION 100 /* 0.1.0 */
+#define TLQ_MAX_ALPHA 64 /* largest alpha grid one call accepts */
+
+typedef enum {
+  TLQ_OK = 0,
+  TLQ_ERR_NULL = 1,        /* a required pointer is NULL */
+  TLQ_ERR_SHAPE = 2,       /* a size is non-positive or inconsistent */
+  TLQ_ERR_UNSUPPORTED = 3, /* a parameter value this build does not implement */
+  TLQ_ERR_WORKSPACE = 4,   /* workspace missing or smaller than the query says */
+  TLQ_ERR_ALIGN = 5,       /* pointer or stride alignment */
+  TLQ_ERR_LAUNCH = 6       /* the HIP runtime rejected a launch */
+} tlq_status;
+
+typedef enum { TLQ_F16 = 0, TLQ_BF16 = 1, TLQ_F32 = 2 } tlq_dtype;
+
+/* Plain-old-data parameter block, passed by const pointer. */
+typedef struct tlq_params {
+  uint32_t struct_size; /* = sizeof(tlq_params); anything else: TLQ_ERR_UNSUPPORTED */
+  int32_t bits;         /* weight bits, 2..8 */
+  int32_t group;        /* input channels per quantisation group; 0 = whole row */
+  int32_t symmetric;    /* 0 = asymmetric min/max grid, 1 = symmetric max|.| grid */
+  int32_t act_bits;     /* must be 0: activations are not quantised */
+  int32_t xstat_kind;   /* 0 = mean |x| over tokens, 1 = max |x| over tokens */
+  int32_t x_dtype;      /* tlq_dtype of X and of W and of the MFMA operands: F16 or BF16 */
+  int32_t yref_dtype;   /* tlq_dtype of Y_ref (and of tlq_ref_output's result) */
+} tlq_params;
+
+const char* tlq_status_string(int status);
+int tlq_version(void);
+
+/* ---- S0: per-channel activation statistic (Sec. 3.1.2, x_stat; mean form of
+ * the ablation table, or max).  x_stat[c] = (1/n_tok) sum_t |X[t,c]| rounded
+ * once to float (sum and division in double), or max_t |X[t,c]|.
+ * x_stat: out, float [c_in]. */
+size_t tlq_x_stat_workspace_bytes(int64_t n_tok, int64_t c_in);
+tlq_status tlq_x_stat(const void* X, int64_t n_tok, int64_t c_in, int64_t ldx,
+                      const tlq_params* p, float* x_stat,
+                      void* workspace, size_t workspace_bytes, void* stream);
+
+/* ---- S1: candidate scales (Sec. 3.1.2 scale eq.; Sec. 3.2.1 per-layer form).
+ * s_table[k,c] = float( pow( double(max(x_stat[c], 2^-14)), double(alpha[k]) ) ).
+ * x_stat: in, float [c_in]; alpha_grid: in, float [n_alpha];
+ * s_table: out, float [n_alpha, c_in]. */
+tlq_status tlq_scale_table(const float* x_stat, int64_t c_in, const float* alpha_grid,
+                           int32_t n_alpha, float* s_table, void* stream);
+
+/* ---- S2: fake quantisation of W * diag(s) (Sec. 2.2 quantiser in min/max
+ * form; Sec. 3.2.1 Q_w(W * scale)).  All grid arithmetic is float, one
+ * rounding per operation, round-half-to-even:
+ *   ws = W*s; rng = max(max_g ws - min_g ws, 1e-5); delta = rng/(2^bits-1);
+ *   zp = clip(rint(-min/delta), 0, 2^bits-1);
+ *   q  = clip(rint(ws/delta) + zp, 0, 2^bits-1);  deq = (q - zp)*delta.
+ * (symmetric=1: delta = max(max_g|ws|,1e-5)/(2^(bits-1)-1), q = clip(rint(ws/
+ * delta), -2^(bits-1), 2^(bits-1)-1), stored codes are q + 2^(bits-1), zp =
+ * 2^(bits-1).)
+ * W: in [c_out, c_in] x_dtype; s: in float [c_in] or NULL (= ones).
+ * Outputs, each may be NULL (skipped): codes uint8 [c_out, c_in] (dense),
+ * zp uint8 [c_out, G], delta float [c_out, G], G = c_in/group;
+ * Wdq [c_out, c_in] x_dtype with row stride ld_dq = deq rounded to x_dtype. */
+tlq_status tlq_fake_quant(const void* W, int64_t c_out, int64_t c_in, int64_t ldw,
+                          const float* s, const tlq_params* p,
+                          uint8_t* codes, uint8_t* zp, float* delta,
+                          void* Wdq, int64_t ld_dq, void* stream);
+
+/* ---- S3+S4 for one given dequantised weight matrix (Sec. 3.2.1 objective
+ * with f_q = (X*inv_s) Wdq^T):
+ *   err[t] = (1/c_out) sum_o (Y_ref[t,o] - sum_c X[t,c]*inv_s[c]*Wdq[o,c])^2
+ *   loss   = sum_t token_w[t] * err[t]
+ * X [n_tok,c_in], Wdq [c_out,c_in]: x_dtype; inv_s: float [c_in] or NULL (ones);
+ * Y_ref [n_tok,c_out] yref_dtype; token_w float [n_tok] (used as given).
+ * loss: out float [1]; per_token_err: out float [n_tok] or NULL. */
+size_t tlq_weighted_layer_err_workspace_bytes(int64_t n_tok, int64_t c_in, int64_t c_out,
+                                              const tlq_params* p);
+tlq_status tlq_weighted_layer_err(const void* X, int64_t n_tok, int64_t c_in, int64_t ldx,
+                                  const void* Wdq, int64_t c_out, int64_t ldw,
+                                  const float* inv_s,
+                                  const void* Y_ref, int64_t ldy, const float* token_w,
+                                  const tlq_params* p, float* loss, float* per_token_err,
+                                  void* workspace, size_t workspace_bytes, void* stream);
+
+/* ---- S0..S5: the search (Sec. 3.2.1: r* = argmin_r E||f_fp(x) - f_q(x; x_stat^r)||^2).
+ * x_stat_in: float [c_in] or NULL (then computed from X per xstat_kind).
+ * alpha_grid: float [n_alpha], 1 <= n_alpha <= TLQ_MAX_ALPHA.
+ * Outputs: best_scales float [c_in] (= s_table[best_idx]); best_idx int32 [1]
+ * (first minimum; -1 if no candidate has a finite loss); losses float
+ * [n_alpha] (+inf where not finite); s_table_out float [n_alpha, c_in] or NULL. */
+size_t tlq_scale_search_workspace_bytes(int64_t n_tok, int64_t c_in, int64_t c_out,
+                                        int32_t n_alpha, const tlq_params* p);
+tlq_status tlq_scale_search(const void* X, int64_t n_tok, int64_t c_in, int64_t ldx,
+                            const void* W, int64_t c_out, int64_t ldw,
+                            const void* Y_ref, int64_t ldy, const float* token_w,
+                            const float* alpha_grid, int32_t n_alpha, const tlq_params* p,
+                            const float* x_stat_in,
+                            float* best_scales, int32_t* best_idx, float* losses,
+                            float* s_table_out,
+                            void* workspace, size_t workspace_bytes, void* stream);
+
+/* ---- full-precision layer output (Sec. 3.2.1 f_fp without bias):
+ * Y[t,o] = sum_c X[t,c] W[o,c], float accumulation, stored as yref_dtype. */
+tlq_status tlq_ref_output(const void* X, int64_t n_tok, int64_t c_in, int64_t ldx,
+                          const void* W, int64_t c_out, int64_t ldw,
+                          void* Y, int64_t ldy, const tlq_params* p, void* stream);
+
+/* ---- S6: quantisation-exposed propagation (Sec. 3.2.1 PassAct2):
+ * X_next = f_q(X; s) = (X diag(s)^-1) Q_w(W diag(s))^T stored as x_dtype.
+ * s: in float [c_in] (e.g. best_scales); X_next: out [n_tok, c_out]. */
+size_t tlq_apply_best_workspace_bytes(int64_t c_in, int64_t c_out, const tlq_params* p);
+tlq_status tlq_apply_best(const void* X, int64_t n_tok, int64_t c_in, int64_t ldx,
+                          const void* W, int64_t c_out, int64_t ldw, const float* s,
+                          const tlq_params* p, void* X_next, int64_t ld_next,
+                          void* workspace, size_t workspace_bytes, void* stream);
+
+/* ---- optional per-kernel timing (host-side bookkeeping only).
+ * While enabled, every kernel the library launches is bracketed by HIP events
+ * on the launch stream.  tlq_profile_collect waits for the recorded events
+ * and folds them into per-kernel totals; tlq_profile_get reads entry i:
+ * kernel name, number of launches, total milliseconds, and the total
+ * algorithmic work (flops for the contraction kernels, bytes otherwise). */
+tlq_status tlq_profile_enable(int on);
+tlq_status tlq_profile_reset(void);
+tlq_status tlq_profile_collect(void);
+int tlq_profile_count(void);
+tlq_status tlq_profile_get(int i, char* name, size_t name_cap, int64_t* launches,
+                           double* total_ms, double* total_work);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* TLQ_H */

@@ -1,0 +1,325 @@
+// C ABI entry points: argument validation, workspace carving, launch plans.
+// Validation touches no HIP API, so every error path returns before anything
+// is enqueued.
+#include "common.h"
+
+using namespace tlq;
+
+namespace {
+
+struct Carver {
+  unsigned char* base; size_t off;
+  explicit Carver(void* p) : base((unsigned char*)p), off(0) {}
+  template <typename T> T* take(size_t count) {
+    T* r = base ? reinterpret_cast<T*>(base + off) : nullptr;
+    off += align_up(count * sizeof(T), 256);
+    return r;
+  }
+};
+
+tlq_status check_params(const tlq_params* p) {
+  if (!p) return TLQ_ERR_NULL;
+  if (p->struct_size != sizeof(tlq_params)) return TLQ_ERR_UNSUPPORTED;
+  if (p->bits < 2 || p->bits > 8) return TLQ_ERR_UNSUPPORTED;
+  if (p->group < 0 || (p->group % 8) != 0) return TLQ_ERR_UNSUPPORTED;
+  if (p->symmetric != 0 && p->symmetric != 1) return TLQ_ERR_UNSUPPORTED;
+  if (p->act_bits != 0) return TLQ_ERR_UNSUPPORTED;
+  if (p->xstat_kind != 0 && p->xstat_kind != 1) return TLQ_ERR_UNSUPPORTED;
+  if (p->x_dtype != TLQ_F16 && p->x_dtype != TLQ_BF16) return TLQ_ERR_UNSUPPORTED;
+  if (p->yref_dtype != TLQ_F16 && p->yref_dtype != TLQ_BF16 && p->yref_dtype != TLQ_F32)
+    return TLQ_ERR_UNSUPPORTED;
+  return TLQ_OK;
+}
+
+bool dims_ok(int64_t rows, int64_t cols, int64_t ld) {
+  return rows > 0 && cols > 0 && ld >= cols && rows < (1LL << 31) && cols < (1LL << 31);
+}
+bool aligned(const void* p, size_t a) { return ((uintptr_t)p % a) == 0; }
+bool mat16_aligned(const void* p, int64_t ld) { return aligned(p, 16) && (ld % 8) == 0; }
+bool mat_aligned(const void* p, int64_t ld, int dtype) {
+  return dtype == TLQ_F32 ? (aligned(p, 16) && (ld % 4) == 0) : mat16_aligned(p, ld);
+}
+tlq_status check_cin(int64_t c_in, const tlq_params* p) {
+  if ((c_in % 8) != 0) return TLQ_ERR_SHAPE;
+  if (p->group != 0 && (c_in % p->group) != 0) return TLQ_ERR_SHAPE;
+  return TLQ_OK;
+}
+tlq_status check_ws(const void* ws, size_t have, size_t need) {
+  if (need == 0) return TLQ_OK;
+  if (!ws || have < need) return TLQ_ERR_WORKSPACE;
+  if (!aligned(ws, 256)) return TLQ_ERR_ALIGN;
+  return TLQ_OK;
+}
+tlq_status hip_status(hipError_t e) { return e == hipSuccess ? TLQ_OK : TLQ_ERR_LAUNCH; }
+
+#define TLQ_TRY(expr) do { tlq_status st_ = (expr); if (st_ != TLQ_OK) return st_; } while (0)
+#define TLQ_HIP(expr) do { if ((expr) != hipSuccess) return TLQ_ERR_LAUNCH; } while (0)
+
+__global__ void recip_kernel(const float* __restrict__ s, int64_t n, float* __restrict__ inv) {
+  const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  if (i < n) inv[i] = (float)(1.0 / (double)s[i]);
+}
+
+// ---- workspace plans -----------------------------------------------------------
+struct SearchPlan {
+  double* xs_partial; float* x_stat; float* s_table; float* inv_table; float* partial;
+  uint16_t* what; size_t bytes; int64_t tiles_o, tiles_t;
+};
+SearchPlan plan_search(void* ws, int64_t n_tok, int64_t c_in, int64_t c_out, int n_alpha) {
+  SearchPlan s;
+  Carver c(ws);
+  gemm_tile_counts(n_tok, c_out, &s.tiles_o, &s.tiles_t);
+  s.xs_partial = c.take<double>((size_t)xstat_chunks(n_tok) * c_in);
+  s.x_stat = c.take<float>((size_t)c_in);
+  s.s_table = c.take<float>((size_t)n_alpha * c_in);
+  s.inv_table = c.take<float>((size_t)n_alpha * c_in);
+  s.partial = c.take<float>((size_t)n_alpha * s.tiles_o * s.tiles_t);
+  s.what = c.take<uint16_t>((size_t)n_alpha * c_out * c_in);
+  s.bytes = c.off;
+  return s;
+}
+
+struct ErrPlan {
+  float* partial; float* tok_partial; uint16_t* folded; size_t bytes; int64_t tiles_o, tiles_t;
+};
+ErrPlan plan_err(void* ws, int64_t n_tok, int64_t c_in, int64_t c_out) {
+  ErrPlan e;
+  Carver c(ws);
+  gemm_tile_counts(n_tok, c_out, &e.tiles_o, &e.tiles_t);
+  e.partial = c.take<float>((size_t)e.tiles_o * e.tiles_t);
+  e.tok_partial = c.take<float>((size_t)e.tiles_o * n_tok);
+  e.folded = c.take<uint16_t>((size_t)c_out * c_in);
+  e.bytes = c.off;
+  return e;
+}
+
+}  // namespace
+
+extern "C" {
+
+const char* tlq_status_string(int s) {
+  switch (s) {
+    case TLQ_OK: return "ok";
+    case TLQ_ERR_NULL: return "required pointer is NULL";
+    case TLQ_ERR_SHAPE: return "invalid or inconsistent shape";
+    case TLQ_ERR_UNSUPPORTED: return "unsupported parameter value";
+    case TLQ_ERR_WORKSPACE: return "workspace missing or too small";
+    case TLQ_ERR_ALIGN: return "pointer or stride not aligned";
+    case TLQ_ERR_LAUNCH: return "HIP launch failed";
+    default: return "unknown status";
+  }
+}
+
+int tlq_version(void) { return TLQ_VERSION; }
+
+// ------------------------------------------------------------------------ S0
+size_t tlq_x_stat_workspace_bytes(int64_t n_tok, int64_t c_in) {
+  if (n_tok <= 0 || c_in <= 0) return 0;
+  return align_up((size_t)xstat_chunks(n_tok) * (size_t)c_in * sizeof(double), 256);
+}
+
+tlq_status tlq_x_stat(const void* X, int64_t n_tok, int64_t c_in, int64_t ldx,
+                      const tlq_params* p, float* x_stat, void* workspace,
+                      size_t workspace_bytes, void* stream) {
+  if (!X || !x_stat) return TLQ_ERR_NULL;
+  TLQ_TRY(check_params(p));
+  if (!dims_ok(n_tok, c_in, ldx) || (c_in % 8) != 0) return TLQ_ERR_SHAPE;
+  if (!mat16_aligned(X, ldx)) return TLQ_ERR_ALIGN;
+  TLQ_TRY(check_ws(workspace, workspace_bytes, tlq_x_stat_workspace_bytes(n_tok, c_in)));
+  return hip_status(launch_xstat(X, n_tok, c_in, ldx, p->x_dtype == TLQ_BF16, p->xstat_kind,
+                                 (double*)workspace, x_stat, (hipStream_t)stream));
+}
+
+// ------------------------------------------------------------------------ S1
+tlq_status tlq_scale_table(const float* x_stat, int64_t c_in, const float* alpha_grid,
+                           int32_t n_alpha, float* s_table, void* stream) {
+  if (!x_stat || !alpha_grid || !s_table) return TLQ_ERR_NULL;
+  if (c_in <= 0 || n_alpha <= 0 || n_alpha > TLQ_MAX_ALPHA) return TLQ_ERR_SHAPE;
+  return hip_status(launch_scale_table(x_stat, c_in, alpha_grid, n_alpha, s_table, nullptr,
+                                       (hipStream_t)stream));
+}
+
+// ------------------------------------------------------------------------ S2
+tlq_status tlq_fake_quant(const void* W, int64_t c_out, int64_t c_in, int64_t ldw,
+                          const float* s, const tlq_params* p, uint8_t* codes, uint8_t* zp,
+                          float* delta, void* Wdq, int64_t ld_dq, void* stream) {
+  if (!W) return TLQ_ERR_NULL;
+  TLQ_TRY(check_params(p));
+  if (!dims_ok(c_out, c_in, ldw)) return TLQ_ERR_SHAPE;
+  TLQ_TRY(check_cin(c_in, p));
+  if (Wdq && ld_dq < c_in) return TLQ_ERR_SHAPE;
+  if (!mat16_aligned(W, ldw)) return TLQ_ERR_ALIGN;
+  if (Wdq && !mat16_aligned(Wdq, ld_dq)) return TLQ_ERR_ALIGN;
+  if ((codes && !aligned(codes, 8)) || (s && !aligned(s, 16)) || (delta && !aligned(delta, 4)))
+    return TLQ_ERR_ALIGN;
+  QuantArgs q{};
+  q.W = W; q.c_out = c_out; q.c_in = c_in; q.ldw = ldw; q.bf16 = p->x_dtype == TLQ_BF16;
+  q.bits = p->bits; q.group = p->group; q.symmetric = p->symmetric;
+  q.s_table = s; q.inv_table = nullptr; q.n_cand = 1;
+  q.what = nullptr; q.what_cand_stride = 0;
+  q.codes = codes; q.zp = zp; q.delta = delta; q.wdq = Wdq; q.ld_dq = ld_dq;
+  return hip_status(launch_fake_quant(q, (hipStream_t)stream));
+}
+
+// -------------------------------------------------------------------- S3 + S4
+size_t tlq_weighted_layer_err_workspace_bytes(int64_t n_tok, int64_t c_in, int64_t c_out,
+                                              const tlq_params* p) {
+  if (n_tok <= 0 || c_in <= 0 || c_out <= 0 || check_params(p) != TLQ_OK) return 0;
+  return plan_err(nullptr, n_tok, c_in, c_out).bytes;
+}
+
+tlq_status tlq_weighted_layer_err(const void* X, int64_t n_tok, int64_t c_in, int64_t ldx,
+                                  const void* Wdq, int64_t c_out, int64_t ldw,
+                                  const float* inv_s, const void* Y_ref, int64_t ldy,
+                                  const float* token_w, const tlq_params* p, float* loss,
+                                  float* per_token_err, void* workspace, size_t workspace_bytes,
+                                  void* stream) {
+  if (!X || !Wdq || !Y_ref || !token_w || !loss) return TLQ_ERR_NULL;
+  TLQ_TRY(check_params(p));
+  if (!dims_ok(n_tok, c_in, ldx) || !dims_ok(c_out, c_in, ldw) || !dims_ok(n_tok, c_out, ldy))
+    return TLQ_ERR_SHAPE;
+  if ((c_in % 8) != 0) return TLQ_ERR_SHAPE;
+  if (!mat16_aligned(X, ldx) || !mat16_aligned(Wdq, ldw) || !mat_aligned(Y_ref, ldy, p->yref_dtype))
+    return TLQ_ERR_ALIGN;
+  TLQ_TRY(check_ws(workspace, workspace_bytes,
+                   tlq_weighted_layer_err_workspace_bytes(n_tok, c_in, c_out, p)));
+  hipStream_t st = (hipStream_t)stream;
+  const bool bf16 = p->x_dtype == TLQ_BF16;
+  ErrPlan e = plan_err(workspace, n_tok, c_in, c_out);
+  GemmArgs g{};
+  g.X = X; g.n_tok = n_tok; g.c_in = c_in; g.ldx = ldx;
+  g.Wh = Wdq; g.c_out = c_out; g.ldw = ldw; g.w_cand_stride = 0; g.n_cand = 1; g.bf16 = bf16;
+  if (inv_s) {
+    TLQ_HIP(launch_fold_scale(Wdq, c_out, c_in, ldw, bf16, inv_s, e.folded, st));
+    g.Wh = e.folded; g.ldw = c_in;
+  }
+  g.Yref = Y_ref; g.ldy = ldy; g.yref_dtype = p->yref_dtype; g.token_w = token_w;
+  g.partial = e.partial; g.tok_partial = per_token_err ? e.tok_partial : nullptr;
+  TLQ_HIP(launch_gemm_loss(g, st));
+  TLQ_HIP(launch_finalize(e.partial, 1, e.tiles_o * e.tiles_t, c_out, nullptr, c_in, loss, nullptr,
+                          nullptr, st));
+  if (per_token_err)
+    TLQ_HIP(launch_token_err_reduce(e.tok_partial, e.tiles_o, n_tok, c_out, per_token_err, st));
+  return TLQ_OK;
+}
+
+// ------------------------------------------------------------------- S0 .. S5
+size_t tlq_scale_search_workspace_bytes(int64_t n_tok, int64_t c_in, int64_t c_out,
+                                        int32_t n_alpha, const tlq_params* p) {
+  if (n_tok <= 0 || c_in <= 0 || c_out <= 0 || n_alpha <= 0 || n_alpha > TLQ_MAX_ALPHA ||
+      check_params(p) != TLQ_OK)
+    return 0;
+  return plan_search(nullptr, n_tok, c_in, c_out, n_alpha).bytes;
+}
+
+tlq_status tlq_scale_search(const void* X, int64_t n_tok, int64_t c_in, int64_t ldx,
+                            const void* W, int64_t c_out, int64_t ldw, const void* Y_ref,
+                            int64_t ldy, const float* token_w, const float* alpha_grid,
+                            int32_t n_alpha, const tlq_params* p, const float* x_stat_in,
+                            float* best_scales, int32_t* best_idx, float* losses,
+                            float* s_table_out, void* workspace, size_t workspace_bytes,
+                            void* stream) {
+  if (!X || !W || !Y_ref || !token_w || !alpha_grid || !best_scales || !best_idx || !losses)
+    return TLQ_ERR_NULL;
+  TLQ_TRY(check_params(p));
+  if (n_alpha <= 0 || n_alpha > TLQ_MAX_ALPHA) return TLQ_ERR_SHAPE;
+  if (!dims_ok(n_tok, c_in, ldx) || !dims_ok(c_out, c_in, ldw) || !dims_ok(n_tok, c_out, ldy))
+    return TLQ_ERR_SHAPE;
+  TLQ_TRY(check_cin(c_in, p));
+  if (!mat16_aligned(X, ldx) || !mat16_aligned(W, ldw) || !mat_aligned(Y_ref, ldy, p->yref_dtype))
+    return TLQ_ERR_ALIGN;
+  TLQ_TRY(check_ws(workspace, workspace_bytes,
+                   tlq_scale_search_workspace_bytes(n_tok, c_in, c_out, n_alpha, p)));
+  hipStream_t st = (hipStream_t)stream;
+  const bool bf16 = p->x_dtype == TLQ_BF16;
+  SearchPlan s = plan_search(workspace, n_tok, c_in, c_out, n_alpha);
+
+  const float* x_stat = x_stat_in;
+  if (!x_stat) {  // S0
+    TLQ_HIP(launch_xstat(X, n_tok, c_in, ldx, bf16, p->xstat_kind, s.xs_partial, s.x_stat, st));
+    x_stat = s.x_stat;
+  }
+  // S1
+  TLQ_HIP(launch_scale_table(x_stat, c_in, alpha_grid, n_alpha, s.s_table, s.inv_table, st));
+  if (s_table_out)
+    TLQ_HIP(hipMemcpyAsync(s_table_out, s.s_table, (size_t)n_alpha * c_in * sizeof(float),
+                           hipMemcpyDeviceToDevice, st));
+  // S2: all candidates' folded operands in one pass over W
+  QuantArgs q{};
+  q.W = W; q.c_out = c_out; q.c_in = c_in; q.ldw = ldw; q.bf16 = bf16;
+  q.bits = p->bits; q.group = p->group; q.symmetric = p->symmetric;
+  q.s_table = s.s_table; q.inv_table = s.inv_table; q.n_cand = n_alpha;
+  q.what = s.what; q.what_cand_stride = c_out * c_in;
+  TLQ_HIP(launch_fake_quant(q, st));
+  // S3 + S4: one launch over the stacked candidates
+  GemmArgs g{};
+  g.X = X; g.n_tok = n_tok; g.c_in = c_in; g.ldx = ldx;
+  g.Wh = s.what; g.c_out = c_out; g.ldw = c_in; g.w_cand_stride = c_out * c_in;
+  g.n_cand = n_alpha; g.bf16 = bf16;
+  g.Yref = Y_ref; g.ldy = ldy; g.yref_dtype = p->yref_dtype; g.token_w = token_w;
+  g.partial = s.partial; g.tok_partial = nullptr;
+  TLQ_HIP(launch_gemm_loss(g, st));
+  // S4 combine + S5
+  TLQ_HIP(launch_finalize(s.partial, n_alpha, s.tiles_o * s.tiles_t, c_out, s.s_table, c_in, losses,
+                          best_idx, best_scales, st));
+  return TLQ_OK;
+}
+
+// ---------------------------------------------------------------- f_fp output
+tlq_status tlq_ref_output(const void* X, int64_t n_tok, int64_t c_in, int64_t ldx,
+                          const void* W, int64_t c_out, int64_t ldw, void* Y, int64_t ldy,
+                          const tlq_params* p, void* stream) {
+  if (!X || !W || !Y) return TLQ_ERR_NULL;
+  TLQ_TRY(check_params(p));
+  if (!dims_ok(n_tok, c_in, ldx) || !dims_ok(c_out, c_in, ldw) || !dims_ok(n_tok, c_out, ldy))
+    return TLQ_ERR_SHAPE;
+  if ((c_in % 8) != 0) return TLQ_ERR_SHAPE;
+  if (!mat16_aligned(X, ldx) || !mat16_aligned(W, ldw) || !mat_aligned(Y, ldy, p->yref_dtype))
+    return TLQ_ERR_ALIGN;
+  GemmArgs g{};
+  g.X = X; g.n_tok = n_tok; g.c_in = c_in; g.ldx = ldx;
+  g.Wh = W; g.c_out = c_out; g.ldw = ldw; g.w_cand_stride = 0; g.n_cand = 1;
+  g.bf16 = p->x_dtype == TLQ_BF16;
+  g.Yout = Y; g.ldo = ldy; g.yout_dtype = p->yref_dtype;
+  return hip_status(launch_gemm_store(g, (hipStream_t)stream));
+}
+
+// ------------------------------------------------------------------------ S6
+size_t tlq_apply_best_workspace_bytes(int64_t c_in, int64_t c_out, const tlq_params* p) {
+  if (c_in <= 0 || c_out <= 0 || check_params(p) != TLQ_OK) return 0;
+  return align_up((size_t)c_in * sizeof(float), 256) + align_up((size_t)c_out * c_in * 2, 256);
+}
+
+tlq_status tlq_apply_best(const void* X, int64_t n_tok, int64_t c_in, int64_t ldx,
+                          const void* W, int64_t c_out, int64_t ldw, const float* s,
+                          const tlq_params* p, void* X_next, int64_t ld_next, void* workspace,
+                          size_t workspace_bytes, void* stream) {
+  if (!X || !W || !s || !X_next) return TLQ_ERR_NULL;
+  TLQ_TRY(check_params(p));
+  if (!dims_ok(n_tok, c_in, ldx) || !dims_ok(c_out, c_in, ldw) || !dims_ok(n_tok, c_out, ld_next))
+    return TLQ_ERR_SHAPE;
+  TLQ_TRY(check_cin(c_in, p));
+  if (!mat16_aligned(X, ldx) || !mat16_aligned(W, ldw) || !mat16_aligned(X_next, ld_next) ||
+      !aligned(s, 16))
+    return TLQ_ERR_ALIGN;
+  TLQ_TRY(check_ws(workspace, workspace_bytes, tlq_apply_best_workspace_bytes(c_in, c_out, p)));
+  hipStream_t st = (hipStream_t)stream;
+  const bool bf16 = p->x_dtype == TLQ_BF16;
+  Carver c(workspace);
+  float* inv = c.take<float>((size_t)c_in);
+  uint16_t* what = c.take<uint16_t>((size_t)c_out * c_in);
+  recip_kernel<<<(unsigned)ceil_div(c_in, 256), 256, 0, st>>>(s, c_in, inv);
+  TLQ_HIP(hipGetLastError());
+  QuantArgs q{};
+  q.W = W; q.c_out = c_out; q.c_in = c_in; q.ldw = ldw; q.bf16 = bf16;
+  q.bits = p->bits; q.group = p->group; q.symmetric = p->symmetric;
+  q.s_table = s; q.inv_table = inv; q.n_cand = 1; q.what = what; q.what_cand_stride = 0;
+  TLQ_HIP(launch_fake_quant(q, st));
+  GemmArgs g{};
+  g.X = X; g.n_tok = n_tok; g.c_in = c_in; g.ldx = ldx;
+  g.Wh = what; g.c_out = c_out; g.ldw = c_in; g.w_cand_stride = 0; g.n_cand = 1; g.bf16 = bf16;
+  g.Yout = X_next; g.ldo = ld_next; g.yout_dtype = p->x_dtype;
+  return hip_status(launch_gemm_store(g, st));
+}
+
+}  // extern "C"

@@ -1,0 +1,338 @@
+// S3 + S4: the candidate-evaluation contraction with the loss fused into its
+// epilogue (Sec. 3.2.1 objective; Sec. 2.2 smoothing identity), and the same
+// contraction with a store epilogue (f_fp of Sec. 3.2.1; PassAct2 output).
+//
+// The kernel computes  D[o, t] = sum_c What[o, c] * X[t, c]  on 32x32x16
+// fp16/bf16 MFMA with float accumulation.  `What` stacks the folded operands
+// of all candidates ([n_cand * c_out, c_in]), so the alpha grid is simply an
+// extra stretch of the o dimension and every X tile is shared by all
+// candidates.  In the loss epilogue each lane owns one token column of its
+// 32x32 fragments: it subtracts the accumulators from Y_ref, squares, sums
+// over its output rows, multiplies by that token's weight and the block
+// reduces to ONE float per (candidate, tile).  Candidate outputs never reach
+// HBM.
+//
+// Tiling (wave64): block tile BO x BT outputs, BK = 64; waves own WO x WT
+// sub-tiles.  Both operands are K-contiguous in memory, so a fragment is one
+// 16-byte LDS read per lane.  LDS rows are 128 B (64 halves) and the eight
+// 16-byte chunks of a row are XOR-swizzled with (row/2)%8 so that the 16 lanes
+// served together by a 128-bit LDS access touch 16 different bank groups, for
+// the fragment reads and for the tile writes alike.
+// Two LDS stages: the global loads of k-tile i+1 are issued before the MFMAs of
+// k-tile i and written to the other stage afterwards; one barrier per k-tile.
+#include "common.h"
+
+namespace tlq {
+
+typedef float f32x16 __attribute__((ext_vector_type(16)));
+typedef _Float16 f16x8 __attribute__((ext_vector_type(8)));
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+
+template <typename T> struct Mma;
+template <> struct Mma<F16> {
+  static __device__ __forceinline__ f32x16 run(const uint4& a, const uint4& b, const f32x16& c) {
+    return __builtin_amdgcn_mfma_f32_32x32x16_f16(__builtin_bit_cast(f16x8, a),
+                                                  __builtin_bit_cast(f16x8, b), c, 0, 0, 0);
+  }
+};
+template <> struct Mma<BF16> {
+  static __device__ __forceinline__ f32x16 run(const uint4& a, const uint4& b, const f32x16& c) {
+    return __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, a),
+                                                   __builtin_bit_cast(bf16x8, b), c, 0, 0, 0);
+  }
+};
+
+enum { EPI_LOSS = 0, EPI_LOSS_TOK = 1, EPI_STORE = 2 };
+constexpr int BK = 64;        // halves per k-tile
+constexpr int ROWB = BK * 2;  // bytes per LDS row
+constexpr int PATCH_O = 4, PATCH_T = 8;  // tiles per L2 patch (one patch per XCD at a time)
+
+struct GemmDev {
+  const uint16_t* X; int64_t n_tok, c_in, ldx;
+  const uint16_t* Wh; int64_t c_out, ldw, w_cand_stride; int n_cand;
+  const void* Yref; int64_t ldy; int ydt; const float* token_w;
+  float* partial; float* tok_partial;
+  void* Yout; int64_t ldo; int odt;
+  int tiles_o, tiles_t, npo, npt;  // tiles per candidate and patches per candidate
+  int64_t n_patches;
+};
+
+__device__ __forceinline__ int swz(int row, int chunk) { return chunk ^ ((row >> 1) & 7); }
+
+__device__ __forceinline__ float load_y(const void* Y, int ydt, int64_t idx) {
+  if (ydt == TLQ_F32) return ((const float*)Y)[idx];
+  const uint16_t b = ((const uint16_t*)Y)[idx];
+  return ydt == TLQ_F16 ? F16::to_float(b) : BF16::to_float(b);
+}
+__device__ __forceinline__ void load_y4(const void* Y, int ydt, int64_t idx, float y[4]) {
+  if (ydt == TLQ_F32) {
+    const float4 v = *reinterpret_cast<const float4*>((const float*)Y + idx);
+    y[0] = v.x; y[1] = v.y; y[2] = v.z; y[3] = v.w;
+  } else {
+    const uint2 v = *reinterpret_cast<const uint2*>((const uint16_t*)Y + idx);
+    if (ydt == TLQ_F16) {
+      y[0] = F16::to_float((uint16_t)v.x); y[1] = F16::to_float((uint16_t)(v.x >> 16));
+      y[2] = F16::to_float((uint16_t)v.y); y[3] = F16::to_float((uint16_t)(v.y >> 16));
+    } else {
+      y[0] = BF16::to_float((uint16_t)v.x); y[1] = BF16::to_float((uint16_t)(v.x >> 16));
+      y[2] = BF16::to_float((uint16_t)v.y); y[3] = BF16::to_float((uint16_t)(v.y >> 16));
+    }
+  }
+}
+__device__ __forceinline__ void store_y4(void* Y, int odt, int64_t idx, const float y[4]) {
+  if (odt == TLQ_F32) {
+    *reinterpret_cast<float4*>((float*)Y + idx) = make_float4(y[0], y[1], y[2], y[3]);
+  } else if (odt == TLQ_F16) {
+    *reinterpret_cast<uint2*>((uint16_t*)Y + idx) =
+        make_uint2((uint32_t)F16::from_float(y[0]) | ((uint32_t)F16::from_float(y[1]) << 16),
+                   (uint32_t)F16::from_float(y[2]) | ((uint32_t)F16::from_float(y[3]) << 16));
+  } else {
+    *reinterpret_cast<uint2*>((uint16_t*)Y + idx) =
+        make_uint2((uint32_t)BF16::from_float(y[0]) | ((uint32_t)BF16::from_float(y[1]) << 16),
+                   (uint32_t)BF16::from_float(y[2]) | ((uint32_t)BF16::from_float(y[3]) << 16));
+  }
+}
+__device__ __forceinline__ void store_y1(void* Y, int odt, int64_t idx, float y) {
+  if (odt == TLQ_F32) ((float*)Y)[idx] = y;
+  else ((uint16_t*)Y)[idx] = odt == TLQ_F16 ? F16::from_float(y) : BF16::from_float(y);
+}
+
+template <typename T, int BO, int BT, int WO, int WT, int EPI>
+__global__ __launch_bounds__((BO / WO) * (BT / WT) * 64) void gemm_kernel(GemmDev a) {
+  constexpr int NWO = BO / WO, NWT = BT / WT, NW = NWO * NWT, NT = NW * 64;
+  constexpr int FA = WO / 32, FB = WT / 32;
+  constexpr int CH_A = BO * 8 / NT, CH_B = BT * 8 / NT;  // 16-byte chunks per thread per k-tile
+  static_assert(BO * 8 % NT == 0 && BT * 8 % NT == 0, "tile/thread mismatch");
+  constexpr int STAGE = (BO + BT) * ROWB;
+  __shared__ __attribute__((aligned(16))) unsigned char lds[2 * STAGE];
+  __shared__ float red[NW];
+
+  // ---- tile of this block: patches of PATCH_O x PATCH_T tiles, one patch per
+  // XCD at a time (blocks are dealt to the 8 XCDs round-robin by block id).
+  const int64_t bid = blockIdx.x;
+  const int64_t round = bid / (8 * PATCH_O * PATCH_T);
+  const int within = (int)(bid % (8 * PATCH_O * PATCH_T));
+  const int64_t patch = round * 8 + (within & 7);
+  const int slot = within >> 3;
+  if (patch >= a.n_patches) return;
+  const int ppc = a.npo * a.npt;
+  const int cand = (int)(patch / ppc);
+  const int prem = (int)(patch % ppc);
+  const int to = (prem / a.npt) * PATCH_O + (slot % PATCH_O);
+  const int tt = (prem % a.npt) * PATCH_T + (slot / PATCH_O);
+  if (to >= a.tiles_o || tt >= a.tiles_t) return;
+  const int64_t o0 = (int64_t)to * BO, t0 = (int64_t)tt * BT;
+
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int wo = wave % NWO, wt = wave / NWO;
+  const uint16_t* Wc = a.Wh + (int64_t)cand * a.w_cand_stride;
+
+  // ---- global -> register staging
+  const uint16_t* pa[CH_A]; bool oka[CH_A]; int la[CH_A];
+  const uint16_t* pb[CH_B]; bool okb[CH_B]; int lb[CH_B];
+  const int lchunk = tid & 7;
+#pragma unroll
+  for (int i = 0; i < CH_A; ++i) {
+    const int r = (i * NT + tid) >> 3;
+    oka[i] = (o0 + r) < a.c_out;
+    pa[i] = Wc + (oka[i] ? (o0 + r) : 0) * a.ldw + lchunk * 8;
+    la[i] = r * ROWB + (swz(r, lchunk) << 4);
+  }
+#pragma unroll
+  for (int i = 0; i < CH_B; ++i) {
+    const int r = (i * NT + tid) >> 3;
+    okb[i] = (t0 + r) < a.n_tok;
+    pb[i] = a.X + (okb[i] ? (t0 + r) : 0) * a.ldx + lchunk * 8;
+    lb[i] = BO * ROWB + r * ROWB + (swz(r, lchunk) << 4);
+  }
+  uint4 ga[CH_A], gb[CH_B];
+  auto gload = [&](int64_t k0) {
+    const bool kok = (k0 + lchunk * 8) < a.c_in;
+#pragma unroll
+    for (int i = 0; i < CH_A; ++i) {
+      ga[i] = make_uint4(0, 0, 0, 0);
+      if (oka[i] && kok) ga[i] = *reinterpret_cast<const uint4*>(pa[i] + k0);
+    }
+#pragma unroll
+    for (int i = 0; i < CH_B; ++i) {
+      gb[i] = make_uint4(0, 0, 0, 0);
+      if (okb[i] && kok) gb[i] = *reinterpret_cast<const uint4*>(pb[i] + k0);
+    }
+  };
+  auto lstore = [&](int stage) {
+    unsigned char* base = lds + stage * STAGE;
+#pragma unroll
+    for (int i = 0; i < CH_A; ++i) *reinterpret_cast<uint4*>(base + la[i]) = ga[i];
+#pragma unroll
+    for (int i = 0; i < CH_B; ++i) *reinterpret_cast<uint4*>(base + lb[i]) = gb[i];
+  };
+
+  // ---- fragment read offsets: lane -> row (lane%32), k-chunk (lane/32) + 2*kk
+  const int frow = lane & 31, fhi = lane >> 5;
+  int offk[4];
+#pragma unroll
+  for (int kk = 0; kk < 4; ++kk) offk[kk] = frow * ROWB + (swz(frow, kk * 2 + fhi) << 4);
+  const int a_base = (wo * WO) * ROWB;
+  const int b_base = BO * ROWB + (wt * WT) * ROWB;
+
+  f32x16 acc[FA][FB];
+#pragma unroll
+  for (int i = 0; i < FA; ++i)
+#pragma unroll
+    for (int j = 0; j < FB; ++j)
+#pragma unroll
+      for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.0f;
+
+  const int64_t nk = (a.c_in + BK - 1) / BK;
+  gload(0);
+  lstore(0);
+  __syncthreads();
+  for (int64_t kt = 0; kt < nk; ++kt) {
+    const int cur = (int)(kt & 1);
+    if (kt + 1 < nk) gload((kt + 1) * BK);
+    const unsigned char* sb = lds + cur * STAGE;
+#pragma unroll
+    for (int kk = 0; kk < 4; ++kk) {
+      uint4 fa[FA], fb[FB];
+#pragma unroll
+      for (int i = 0; i < FA; ++i)
+        fa[i] = *reinterpret_cast<const uint4*>(sb + a_base + i * 32 * ROWB + offk[kk]);
+#pragma unroll
+      for (int j = 0; j < FB; ++j)
+        fb[j] = *reinterpret_cast<const uint4*>(sb + b_base + j * 32 * ROWB + offk[kk]);
+#pragma unroll
+      for (int i = 0; i < FA; ++i)
+#pragma unroll
+        for (int j = 0; j < FB; ++j) acc[i][j] = Mma<T>::run(fa[i], fb[j], acc[i][j]);
+    }
+    if (kt + 1 < nk) lstore(cur ^ 1);
+    __syncthreads();
+  }
+
+  // ---- epilogue.  Accumulator layout of a 32x32 fragment: lane holds column
+  // (lane%32) and rows 8*(v/4) + 4*(lane/32) + v%4 for v = 0..15.
+  if (EPI == EPI_STORE) {
+#pragma unroll
+    for (int j = 0; j < FB; ++j) {
+      const int64_t t = t0 + wt * WT + j * 32 + frow;
+      if (t >= a.n_tok) continue;
+#pragma unroll
+      for (int i = 0; i < FA; ++i)
+#pragma unroll
+        for (int q = 0; q < 4; ++q) {
+          const int64_t o = o0 + wo * WO + i * 32 + q * 8 + fhi * 4;
+          float y[4] = {acc[i][j][q * 4], acc[i][j][q * 4 + 1], acc[i][j][q * 4 + 2], acc[i][j][q * 4 + 3]};
+          if (o + 3 < a.c_out) store_y4(a.Yout, a.odt, t * a.ldo + o, y);
+          else
+            for (int r = 0; r < 4; ++r)
+              if (o + r < a.c_out) store_y1(a.Yout, a.odt, t * a.ldo + o + r, y[r]);
+        }
+    }
+    return;
+  }
+
+  float part = 0.0f;
+  float* rows = reinterpret_cast<float*>(lds);  // [NWO][BT] row sums, reuses the tile memory
+#pragma unroll
+  for (int j = 0; j < FB; ++j) {
+    const int64_t t = t0 + wt * WT + j * 32 + frow;
+    const bool tok = t < a.n_tok;
+    float sumsq = 0.0f;
+    if (tok) {
+#pragma unroll
+      for (int i = 0; i < FA; ++i)
+#pragma unroll
+        for (int q = 0; q < 4; ++q) {
+          const int64_t o = o0 + wo * WO + i * 32 + q * 8 + fhi * 4;
+          if (o + 3 < a.c_out) {
+            float y[4];
+            load_y4(a.Yref, a.ydt, t * a.ldy + o, y);
+#pragma unroll
+            for (int r = 0; r < 4; ++r) {
+              const float d = y[r] - acc[i][j][q * 4 + r];
+              sumsq += d * d;
+            }
+          } else {
+            for (int r = 0; r < 4; ++r)
+              if (o + r < a.c_out) {
+                const float d = load_y(a.Yref, a.ydt, t * a.ldy + o + r) - acc[i][j][q * 4 + r];
+                sumsq += d * d;
+              }
+          }
+        }
+      part += a.token_w[t] * sumsq;
+    }
+    if (EPI == EPI_LOSS_TOK) {
+      const float both = sumsq + __shfl_xor(sumsq, 32, 64);
+      if (fhi == 0) rows[wo * BT + wt * WT + j * 32 + frow] = both;
+    }
+  }
+#pragma unroll
+  for (int off = 32; off >= 1; off >>= 1) part += __shfl_xor(part, off, 64);
+  if (lane == 0) red[wave] = part;
+  __syncthreads();
+  if (tid == 0) {
+    float s = 0.0f;
+#pragma unroll
+    for (int w = 0; w < NW; ++w) s += red[w];
+    a.partial[((int64_t)cand * a.tiles_o + to) * a.tiles_t + tt] = s;
+  }
+  if (EPI == EPI_LOSS_TOK) {
+    for (int i = tid; i < BT; i += NT) {
+      const int64_t t = t0 + i;
+      if (t < a.n_tok) {
+        float s = 0.0f;
+#pragma unroll
+        for (int w = 0; w < NWO; ++w) s += rows[w * BT + i];
+        a.tok_partial[(int64_t)to * a.n_tok + t] = s;
+      }
+    }
+  }
+}
+
+// ---- host side ---------------------------------------------------------------
+constexpr int kBO = 256, kBT = 256, kWO = 128, kWT = 64;
+
+void gemm_tile_counts(int64_t n_tok, int64_t c_out, int64_t* tiles_o, int64_t* tiles_t) {
+  *tiles_o = ceil_div(c_out, kBO);
+  *tiles_t = ceil_div(n_tok, kBT);
+}
+
+static GemmDev make_dev(const GemmArgs& g) {
+  GemmDev d;
+  d.X = (const uint16_t*)g.X; d.n_tok = g.n_tok; d.c_in = g.c_in; d.ldx = g.ldx;
+  d.Wh = (const uint16_t*)g.Wh; d.c_out = g.c_out; d.ldw = g.ldw;
+  d.w_cand_stride = g.w_cand_stride; d.n_cand = g.n_cand;
+  d.Yref = g.Yref; d.ldy = g.ldy; d.ydt = g.yref_dtype; d.token_w = g.token_w;
+  d.partial = g.partial; d.tok_partial = g.tok_partial;
+  d.Yout = g.Yout; d.ldo = g.ldo; d.odt = g.yout_dtype;
+  int64_t to, tt;
+  gemm_tile_counts(g.n_tok, g.c_out, &to, &tt);
+  d.tiles_o = (int)to; d.tiles_t = (int)tt;
+  d.npo = (int)ceil_div(to, PATCH_O); d.npt = (int)ceil_div(tt, PATCH_T);
+  d.n_patches = (int64_t)g.n_cand * d.npo * d.npt;
+  return d;
+}
+
+template <int EPI>
+static hipError_t launch_gemm(const GemmArgs& g, const char* name, hipStream_t stream) {
+  GemmDev d = make_dev(g);
+  const int64_t rounds = ceil_div(d.n_patches, 8);
+  const int64_t blocks = rounds * 8 * PATCH_O * PATCH_T;
+  if (blocks > 0x7fffffffLL) return hipErrorInvalidValue;
+  ProfScope ps(name, stream, 2.0 * (double)g.n_tok * (double)g.c_in * (double)g.c_out * g.n_cand);
+  constexpr int NT = (kBO / kWO) * (kBT / kWT) * 64;
+  if (!g.bf16) gemm_kernel<F16, kBO, kBT, kWO, kWT, EPI><<<(unsigned)blocks, NT, 0, stream>>>(d);
+  else gemm_kernel<BF16, kBO, kBT, kWO, kWT, EPI><<<(unsigned)blocks, NT, 0, stream>>>(d);
+  return hipGetLastError();
+}
+
+hipError_t launch_gemm_loss(const GemmArgs& g, hipStream_t stream) {
+  if (g.tok_partial) return launch_gemm<EPI_LOSS_TOK>(g, "gemm_loss_tok", stream);
+  return launch_gemm<EPI_LOSS>(g, "gemm_loss", stream);
+}
+hipError_t launch_gemm_store(const GemmArgs& g, hipStream_t stream) {
+  return launch_gemm<EPI_STORE>(g, "gemm_store", stream);
+}
+
+}  // namespace tlq

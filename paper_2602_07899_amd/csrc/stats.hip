@@ -1,0 +1,192 @@
+// S0 (x_stat), S1 (scale table), the final loss combine and S5 (selection).
+// All HBM-bound or tiny; none uses floating-point atomics, so results are
+// bit-identical from run to run.
+#include "common.h"
+
+namespace tlq {
+
+// ---------------------------------------------------------------- S0 x_stat
+// Sec. 3.1.2 x_stat (mean variant of the ablation table, or max over all
+// tokens).  Each lane owns 8 consecutive channels (one 16-byte load per row);
+// the 4 waves of a block walk interleaved rows of the block's row chunk and
+// are combined through LDS; chunks are combined by a second kernel.  Sums are
+// carried in double: |fp16| values are multiples of 2^-24 below 2^16, so the
+// sum over up to 2^37 tokens is exact and the order of addition is immaterial.
+constexpr int kXsThreads = 256;
+constexpr int kXsCols = 64 * 8;  // channels per block
+
+int xstat_chunks(int64_t n_tok) {
+  int64_t c = ceil_div(n_tok, 128);
+  return (int)(c < 1 ? 1 : (c > 128 ? 128 : c));
+}
+
+template <typename T, int KIND>
+__global__ __launch_bounds__(kXsThreads) void xstat_partial_kernel(
+    const uint16_t* __restrict__ X, int64_t n_tok, int64_t c_in, int64_t ldx, int rows_per_chunk,
+    double* __restrict__ partial) {
+  __shared__ double red[4][kXsCols];
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int64_t c0 = (int64_t)blockIdx.x * kXsCols + lane * 8;
+  const int64_t r0 = (int64_t)blockIdx.y * rows_per_chunk;
+  int64_t r1 = r0 + rows_per_chunk;
+  if (r1 > n_tok) r1 = n_tok;
+  double acc[8];
+#pragma unroll
+  for (int j = 0; j < 8; ++j) acc[j] = 0.0;
+  if (c0 < c_in) {
+    for (int64_t r = r0 + wave; r < r1; r += 4) {
+      const uint4 v = *reinterpret_cast<const uint4*>(X + r * ldx + c0);
+      const uint32_t w[4] = {v.x, v.y, v.z, v.w};
+#pragma unroll
+      for (int j = 0; j < 8; ++j) {
+        const uint16_t b = (uint16_t)((w[j >> 1] >> ((j & 1) * 16)) & 0x7fffu);  // |x|
+        const double a = (double)T::to_float(b);
+        if (KIND == 0) acc[j] += a; else acc[j] = a > acc[j] ? a : acc[j];
+      }
+    }
+  }
+#pragma unroll
+  for (int j = 0; j < 8; ++j) red[wave][lane * 8 + j] = acc[j];
+  __syncthreads();
+  for (int i = threadIdx.x; i < kXsCols; i += kXsThreads) {
+    const int64_t c = (int64_t)blockIdx.x * kXsCols + i;
+    if (c < c_in) {
+      double s;
+      if (KIND == 0) s = ((red[0][i] + red[1][i]) + red[2][i]) + red[3][i];
+      else s = fmax(fmax(red[0][i], red[1][i]), fmax(red[2][i], red[3][i]));
+      partial[(int64_t)blockIdx.y * c_in + c] = s;
+    }
+  }
+}
+
+template <int KIND>
+__global__ void xstat_final_kernel(const double* __restrict__ partial, int n_chunks, int64_t c_in,
+                                   int64_t n_tok, float* __restrict__ x_stat) {
+  const int64_t c = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  if (c >= c_in) return;
+  double s = 0.0;
+  for (int i = 0; i < n_chunks; ++i) {
+    const double v = partial[(int64_t)i * c_in + c];
+    if (KIND == 0) s += v; else s = v > s ? v : s;
+  }
+  x_stat[c] = (float)(KIND == 0 ? s / (double)n_tok : s);
+}
+
+hipError_t launch_xstat(const void* X, int64_t n_tok, int64_t c_in, int64_t ldx, bool bf16,
+                        int kind, double* partial, float* x_stat, hipStream_t stream) {
+  const int chunks = xstat_chunks(n_tok);
+  const int rows = (int)ceil_div(n_tok, chunks);
+  dim3 grid((unsigned)ceil_div(c_in, kXsCols), (unsigned)chunks);
+  const uint16_t* x = (const uint16_t*)X;
+  {
+    ProfScope ps("xstat_partial", stream, 2.0 * (double)n_tok * (double)c_in);
+    if (!bf16 && kind == 0) xstat_partial_kernel<F16, 0><<<grid, kXsThreads, 0, stream>>>(x, n_tok, c_in, ldx, rows, partial);
+    else if (!bf16) xstat_partial_kernel<F16, 1><<<grid, kXsThreads, 0, stream>>>(x, n_tok, c_in, ldx, rows, partial);
+    else if (kind == 0) xstat_partial_kernel<BF16, 0><<<grid, kXsThreads, 0, stream>>>(x, n_tok, c_in, ldx, rows, partial);
+    else xstat_partial_kernel<BF16, 1><<<grid, kXsThreads, 0, stream>>>(x, n_tok, c_in, ldx, rows, partial);
+  }
+  hipError_t e = hipGetLastError();
+  if (e != hipSuccess) return e;
+  {
+    ProfScope ps("xstat_final", stream, 8.0 * (double)chunks * (double)c_in);
+    const unsigned g2 = (unsigned)ceil_div(c_in, 256);
+    if (kind == 0) xstat_final_kernel<0><<<g2, 256, 0, stream>>>(partial, chunks, c_in, n_tok, x_stat);
+    else xstat_final_kernel<1><<<g2, 256, 0, stream>>>(partial, chunks, c_in, n_tok, x_stat);
+  }
+  return hipGetLastError();
+}
+
+// ------------------------------------------------------------ S1 scale table
+// Sec. 3.1.2 scale equation: s = x_stat^alpha, evaluated in double and rounded
+// once; the reciprocal table feeds the folded GEMM operand deq / s.
+__global__ void scale_table_kernel(const float* __restrict__ x_stat, int64_t c_in,
+                                   const float* __restrict__ alpha, int n_alpha,
+                                   float* __restrict__ s_table, float* __restrict__ inv_table) {
+  const int64_t c = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  const int k = blockIdx.y;
+  if (c >= c_in || k >= n_alpha) return;
+  float xs = x_stat[c];
+  xs = xs > kXstatFloor ? xs : kXstatFloor;  // also maps NaN to the floor
+  const float s = (float)pow((double)xs, (double)alpha[k]);
+  s_table[(int64_t)k * c_in + c] = s;
+  if (inv_table) inv_table[(int64_t)k * c_in + c] = (float)(1.0 / (double)s);
+}
+
+hipError_t launch_scale_table(const float* x_stat, int64_t c_in, const float* alpha, int n_alpha,
+                              float* s_table, float* inv_table, hipStream_t stream) {
+  ProfScope ps("scale_table", stream, 8.0 * (double)n_alpha * (double)c_in);
+  dim3 grid((unsigned)ceil_div(c_in, 256), (unsigned)n_alpha);
+  scale_table_kernel<<<grid, 256, 0, stream>>>(x_stat, c_in, alpha, n_alpha, s_table, inv_table);
+  return hipGetLastError();
+}
+
+// ------------------------------------------- final combine (S4) + select (S5)
+// One block.  Wave k sums candidate k's tile partials in double in a fixed
+// order (lane-strided, then a fixed butterfly), scales by 1/c_out, and stores
+// the loss as float (+inf if not finite).  Thread 0 then picks the first
+// minimum (Sec. 3.2.1 argmin) and the block copies that row of the table.
+__global__ __launch_bounds__(1024) void finalize_kernel(
+    const float* __restrict__ partial, int n_cand, int64_t tiles_per_cand, double inv_c_out,
+    const float* __restrict__ s_table, int64_t c_in, float* __restrict__ losses,
+    int32_t* __restrict__ best_idx, float* __restrict__ best_scales) {
+  __shared__ float sl[TLQ_MAX_ALPHA];
+  __shared__ int sbest;
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6, nwaves = blockDim.x >> 6;
+  for (int k = wave; k < n_cand; k += nwaves) {
+    double acc = 0.0;
+    const float* p = partial + (int64_t)k * tiles_per_cand;
+    for (int64_t i = lane; i < tiles_per_cand; i += 64) acc += (double)p[i];
+#pragma unroll
+    for (int off = 32; off >= 1; off >>= 1) acc += __shfl_xor(acc, off, 64);
+    if (lane == 0) {
+      float l = (float)(acc * inv_c_out);
+      if (!(l == l) || l == __builtin_inff() || l == -__builtin_inff()) l = __builtin_inff();
+      sl[k] = l;
+      losses[k] = l;
+    }
+  }
+  __syncthreads();
+  if (threadIdx.x == 0) {
+    int b = -1;
+    float bl = __builtin_inff();
+    for (int k = 0; k < n_cand; ++k)
+      if (sl[k] < bl) { bl = sl[k]; b = k; }
+    sbest = b;
+    if (best_idx) *best_idx = b;
+  }
+  __syncthreads();
+  if (best_scales) {
+    const int b = sbest;
+    for (int64_t c = threadIdx.x; c < c_in; c += blockDim.x)
+      best_scales[c] = b >= 0 ? s_table[(int64_t)b * c_in + c] : __builtin_nanf("");
+  }
+}
+
+hipError_t launch_finalize(const float* partial, int n_cand, int64_t tiles_per_cand, int64_t c_out,
+                           const float* s_table, int64_t c_in, float* losses, int32_t* best_idx,
+                           float* best_scales, hipStream_t stream) {
+  ProfScope ps("finalize", stream, 4.0 * (double)n_cand * (double)tiles_per_cand);
+  finalize_kernel<<<1, 1024, 0, stream>>>(partial, n_cand, tiles_per_cand, 1.0 / (double)c_out,
+                                          s_table, c_in, losses, best_idx, best_scales);
+  return hipGetLastError();
+}
+
+// per_token_err[t] = (1/c_out) * sum over o-tiles of the tile row sums
+__global__ void token_err_reduce_kernel(const float* __restrict__ tok_partial, int64_t tiles_o,
+                                        int64_t n_tok, double inv_c_out, float* __restrict__ out) {
+  const int64_t t = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  if (t >= n_tok) return;
+  double acc = 0.0;
+  for (int64_t i = 0; i < tiles_o; ++i) acc += (double)tok_partial[i * n_tok + t];
+  out[t] = (float)(acc * inv_c_out);
+}
+
+hipError_t launch_token_err_reduce(const float* tok_partial, int64_t tiles_o, int64_t n_tok,
+                                   int64_t c_out, float* per_token_err, hipStream_t stream) {
+  ProfScope ps("token_err_reduce", stream, 4.0 * (double)tiles_o * (double)n_tok);
+  token_err_reduce_kernel<<<(unsigned)ceil_div(n_tok, 256), 256, 0, stream>>>(
+      tok_partial, tiles_o, n_tok, 1.0 / (double)c_out, per_token_err);
+  return hipGetLastError();
+}
+
+}  // namespace tlq

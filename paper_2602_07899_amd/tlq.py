@@ -1,0 +1,227 @@
+"""Thin ctypes binding of libtlq.so (same names as include/tlq.h).
+
+Argument marshalling only: every step of the path runs in the library's HIP
+kernels.  Tensors are torch CUDA(ROCm) tensors used as device memory; work is
+enqueued on torch's current stream.  The library is loaded on first use and a
+missing build is an error - there is no fallback path.
+"""
+from __future__ import annotations
+
+import ctypes as C
+import os
+from dataclasses import dataclass
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libtlq.so")
+
+OK, ERR_NULL, ERR_SHAPE, ERR_UNSUPPORTED, ERR_WORKSPACE, ERR_ALIGN, ERR_LAUNCH = range(7)
+F16, BF16, F32 = 0, 1, 2
+MAX_ALPHA = 64
+
+
+class Params(C.Structure):
+    _fields_ = [("struct_size", C.c_uint32), ("bits", C.c_int32), ("group", C.c_int32),
+                ("symmetric", C.c_int32), ("act_bits", C.c_int32), ("xstat_kind", C.c_int32),
+                ("x_dtype", C.c_int32), ("yref_dtype", C.c_int32)]
+
+
+def params(bits=4, group=128, symmetric=0, act_bits=0, xstat_kind=0, x_dtype=F16, yref_dtype=F16):
+    return Params(C.sizeof(Params), bits, group, symmetric, act_bits, xstat_kind, x_dtype, yref_dtype)
+
+
+class TlqError(RuntimeError):
+    def __init__(self, status, where):
+        self.status = status
+        super().__init__(f"{where}: {status_string(status)} (status {status})")
+
+
+_lib = None
+
+_P = C.c_void_p
+_I64 = C.c_int64
+_I32 = C.c_int32
+_SZ = C.c_size_t
+_PP = C.POINTER(Params)
+
+_SIGNATURES = {
+    "tlq_status_string": (C.c_char_p, [C.c_int]),
+    "tlq_version": (C.c_int, []),
+    "tlq_x_stat_workspace_bytes": (_SZ, [_I64, _I64]),
+    "tlq_x_stat": (C.c_int, [_P, _I64, _I64, _I64, _PP, _P, _P, _SZ, _P]),
+    "tlq_scale_table": (C.c_int, [_P, _I64, _P, _I32, _P, _P]),
+    "tlq_fake_quant": (C.c_int, [_P, _I64, _I64, _I64, _P, _PP, _P, _P, _P, _P, _I64, _P]),
+    "tlq_weighted_layer_err_workspace_bytes": (_SZ, [_I64, _I64, _I64, _PP]),
+    "tlq_weighted_layer_err": (C.c_int, [_P, _I64, _I64, _I64, _P, _I64, _I64, _P, _P, _I64, _P,
+                                         _PP, _P, _P, _P, _SZ, _P]),
+    "tlq_scale_search_workspace_bytes": (_SZ, [_I64, _I64, _I64, _I32, _PP]),
+    "tlq_scale_search": (C.c_int, [_P, _I64, _I64, _I64, _P, _I64, _I64, _P, _I64, _P, _P, _I32,
+                                   _PP, _P, _P, _P, _P, _P, _P, _SZ, _P]),
+    "tlq_ref_output": (C.c_int, [_P, _I64, _I64, _I64, _P, _I64, _I64, _P, _I64, _PP, _P]),
+    "tlq_apply_best_workspace_bytes": (_SZ, [_I64, _I64, _PP]),
+    "tlq_apply_best": (C.c_int, [_P, _I64, _I64, _I64, _P, _I64, _I64, _P, _PP, _P, _I64, _P, _SZ, _P]),
+    "tlq_profile_enable": (C.c_int, [C.c_int]),
+    "tlq_profile_reset": (C.c_int, []),
+    "tlq_profile_collect": (C.c_int, []),
+    "tlq_profile_count": (C.c_int, []),
+    "tlq_profile_get": (C.c_int, [C.c_int, C.c_char_p, _SZ, C.POINTER(C.c_int64),
+                                  C.POINTER(C.c_double), C.POINTER(C.c_double)]),
+}
+EXPORTS = tuple(_SIGNATURES)
+
+
+def lib():
+    """Load libtlq.so (once).  Raises if it has not been built."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(LIB_PATH):
+            raise RuntimeError(f"{LIB_PATH} is missing: build it with "
+                               "`python -m paper_2602_07899_amd.build` (no fallback path exists)")
+        l = C.CDLL(LIB_PATH)
+        for name, (res, args) in _SIGNATURES.items():
+            fn = getattr(l, name)
+            fn.restype, fn.argtypes = res, args
+        _lib = l
+    return _lib
+
+
+def status_string(status: int) -> str:
+    return lib().tlq_status_string(int(status)).decode()
+
+
+def version() -> int:
+    return lib().tlq_version()
+
+
+def _check(status, where):
+    if status != OK:
+        raise TlqError(status, where)
+
+
+def _ptr(t):
+    return None if t is None else C.c_void_p(t.data_ptr())
+
+
+def _stream():
+    import torch
+    return C.c_void_p(torch.cuda.current_stream().cuda_stream)
+
+
+def _ws(nbytes, like):
+    import torch
+    return torch.empty(max(int(nbytes), 256), dtype=torch.uint8, device=like.device)
+
+
+def _ld(t):
+    assert t.dim() == 2 and t.stride(1) == 1, "matrices must be row-major with unit column stride"
+    return t.stride(0)
+
+
+# ------------------------------------------------------------------ entry points
+def x_stat_workspace_bytes(n_tok, c_in):
+    return lib().tlq_x_stat_workspace_bytes(n_tok, c_in)
+
+
+def x_stat(X, p, out, workspace=None):
+    n, c = X.shape
+    ws = workspace if workspace is not None else _ws(x_stat_workspace_bytes(n, c), X)
+    _check(lib().tlq_x_stat(_ptr(X), n, c, _ld(X), C.byref(p), _ptr(out), _ptr(ws), ws.numel(),
+                            _stream()), "tlq_x_stat")
+    return out
+
+
+def scale_table(x_stat_t, alpha_grid, out):
+    _check(lib().tlq_scale_table(_ptr(x_stat_t), x_stat_t.numel(), _ptr(alpha_grid),
+                                 alpha_grid.numel(), _ptr(out), _stream()), "tlq_scale_table")
+    return out
+
+
+def fake_quant(W, s, p, codes=None, zp=None, delta=None, Wdq=None):
+    co, ci = W.shape
+    _check(lib().tlq_fake_quant(_ptr(W), co, ci, _ld(W), _ptr(s), C.byref(p), _ptr(codes), _ptr(zp),
+                                _ptr(delta), _ptr(Wdq), 0 if Wdq is None else _ld(Wdq), _stream()),
+           "tlq_fake_quant")
+
+
+def weighted_layer_err_workspace_bytes(n_tok, c_in, c_out, p):
+    return lib().tlq_weighted_layer_err_workspace_bytes(n_tok, c_in, c_out, C.byref(p))
+
+
+def weighted_layer_err(X, Wdq, inv_s, Y_ref, token_w, p, loss, per_token_err=None, workspace=None):
+    n, ci = X.shape
+    co = Wdq.shape[0]
+    ws = workspace if workspace is not None else _ws(
+        weighted_layer_err_workspace_bytes(n, ci, co, p), X)
+    _check(lib().tlq_weighted_layer_err(_ptr(X), n, ci, _ld(X), _ptr(Wdq), co, _ld(Wdq), _ptr(inv_s),
+                                        _ptr(Y_ref), _ld(Y_ref), _ptr(token_w), C.byref(p),
+                                        _ptr(loss), _ptr(per_token_err), _ptr(ws), ws.numel(),
+                                        _stream()), "tlq_weighted_layer_err")
+    return loss
+
+
+def scale_search_workspace_bytes(n_tok, c_in, c_out, n_alpha, p):
+    return lib().tlq_scale_search_workspace_bytes(n_tok, c_in, c_out, n_alpha, C.byref(p))
+
+
+def scale_search(X, W, Y_ref, token_w, alpha_grid, p, best_scales, best_idx, losses,
+                 x_stat_in=None, s_table_out=None, workspace=None):
+    n, ci = X.shape
+    co = W.shape[0]
+    na = alpha_grid.numel()
+    ws = workspace if workspace is not None else _ws(scale_search_workspace_bytes(n, ci, co, na, p), X)
+    _check(lib().tlq_scale_search(_ptr(X), n, ci, _ld(X), _ptr(W), co, _ld(W), _ptr(Y_ref),
+                                  _ld(Y_ref), _ptr(token_w), _ptr(alpha_grid), na, C.byref(p),
+                                  _ptr(x_stat_in), _ptr(best_scales), _ptr(best_idx), _ptr(losses),
+                                  _ptr(s_table_out), _ptr(ws), ws.numel(), _stream()),
+           "tlq_scale_search")
+
+
+def ref_output(X, W, Y, p):
+    n, ci = X.shape
+    co = W.shape[0]
+    _check(lib().tlq_ref_output(_ptr(X), n, ci, _ld(X), _ptr(W), co, _ld(W), _ptr(Y), _ld(Y),
+                                C.byref(p), _stream()), "tlq_ref_output")
+    return Y
+
+
+def apply_best_workspace_bytes(c_in, c_out, p):
+    return lib().tlq_apply_best_workspace_bytes(c_in, c_out, C.byref(p))
+
+
+def apply_best(X, W, s, p, X_next, workspace=None):
+    n, ci = X.shape
+    co = W.shape[0]
+    ws = workspace if workspace is not None else _ws(apply_best_workspace_bytes(ci, co, p), X)
+    _check(lib().tlq_apply_best(_ptr(X), n, ci, _ld(X), _ptr(W), co, _ld(W), _ptr(s), C.byref(p),
+                                _ptr(X_next), _ld(X_next), _ptr(ws), ws.numel(), _stream()),
+           "tlq_apply_best")
+    return X_next
+
+
+# ------------------------------------------------------------------ profiling
+@dataclass
+class KernelTime:
+    name: str
+    launches: int
+    total_ms: float
+    total_work: float
+
+
+def profile_enable(on: bool):
+    _check(lib().tlq_profile_enable(1 if on else 0), "tlq_profile_enable")
+
+
+def profile_reset():
+    _check(lib().tlq_profile_reset(), "tlq_profile_reset")
+
+
+def profile_read():
+    """Wait for recorded events and return the per-kernel totals."""
+    l = lib()
+    _check(l.tlq_profile_collect(), "tlq_profile_collect")
+    out = []
+    for i in range(l.tlq_profile_count()):
+        name = C.create_string_buffer(64)
+        n, ms, work = C.c_int64(), C.c_double(), C.c_double()
+        _check(l.tlq_profile_get(i, name, 64, C.byref(n), C.byref(ms), C.byref(work)), "tlq_profile_get")
+        out.append(KernelTime(name.value.decode(), n.value, ms.value, work.value))
+    return out

@@ -1,0 +1,400 @@
+"""GPU parity: the HIP path (through the C ABI) against the CPU oracle on the
+same seeded inputs.  Integer work (codes, zero points, selected index) and the
+fp32 grid steps must match bit for bit; losses within 1e-3 relative (the bar
+the task states); the chosen alpha must be identical unless the oracle's two
+best losses are within that tolerance of each other."""
+import numpy as np
+import pytest
+
+from oracle import tlq_oracle as orc
+from paper_2602_07899_amd import tlq
+from paper_2602_07899_amd import workloads as wl
+
+pytestmark = pytest.mark.gpu
+LOSS_RTOL = 1e-3
+
+
+# ----------------------------------------------------------------- helpers
+def dev(a, gpu, bf16=False):
+    import torch
+    t = torch.from_numpy(np.ascontiguousarray(a))
+    if bf16:
+        t = t.to(torch.bfloat16)
+    return t.to(gpu)
+
+
+def host(t):
+    import torch
+    if t.dtype == torch.bfloat16:
+        t = t.float()
+    return t.detach().cpu().numpy()
+
+
+def empty(shape, dtype, gpu):
+    import torch
+    return torch.empty(shape, dtype=dtype, device=gpu)
+
+
+def as_bf16_values(a):
+    """float32 array holding exactly bf16-representable values."""
+    return orc.round_to_bf16(np.asarray(a, np.float32))
+
+
+def run_fake_quant(W_np, s_np, p, gpu, bf16=False):
+    import torch
+    W = dev(W_np, gpu, bf16)
+    co, ci = W_np.shape
+    g = ci if p.group == 0 else p.group
+    codes = empty((co, ci), torch.uint8, gpu)
+    zp = empty((co, ci // g), torch.uint8, gpu)
+    delta = empty((co, ci // g), torch.float32, gpu)
+    wdq = torch.empty_like(W)
+    s = None if s_np is None else dev(s_np, gpu)
+    tlq.fake_quant(W, s, p, codes, zp, delta, wdq)
+    torch.cuda.synchronize()
+    return host(codes), host(zp), host(delta), host(wdq)
+
+
+def check_losses(gpu_losses, orc_losses, gpu_best, where=""):
+    gl = np.asarray(gpu_losses, np.float64)
+    ol = np.asarray(orc_losses, np.float64)
+    rel = np.abs(gl - ol) / ol
+    assert np.all(rel < LOSS_RTOL), f"{where} loss mismatch: max rel {rel.max():.3e}"
+    ob = orc.select_best(ol)
+    if gpu_best != ob:
+        srt = np.sort(ol)
+        assert (srt[1] - srt[0]) / srt[0] < LOSS_RTOL, f"{where} argmin differs: {gpu_best} vs {ob}"
+        assert abs(ol[gpu_best] - ol[ob]) / ol[ob] < LOSS_RTOL
+    return float(rel.max())
+
+
+# --------------------------------------------------------------- S0 x_stat
+@pytest.mark.parametrize("n,c,kind", [(256, 512, 0), (1000, 1096, 0), (3, 8, 0), (20000, 520, 0),
+                                      (777, 1024, 1)])
+def test_x_stat_bit_exact(gpu, n, c, kind):
+    import torch
+    rng = np.random.default_rng(n + c)
+    X = (rng.standard_normal((n, c)) * rng.uniform(0.01, 30, c)).astype(np.float16)
+    p = tlq.params(xstat_kind=kind)
+    for bf16 in (False, True):
+        Xv = as_bf16_values(X) if bf16 else X
+        out = empty((c,), torch.float32, gpu)
+        p.x_dtype = tlq.BF16 if bf16 else tlq.F16
+        tlq.x_stat(dev(Xv, gpu, bf16), p, out)
+        ref = orc.x_stat_mean(Xv) if kind == 0 else orc.x_stat_max(Xv)
+        assert np.array_equal(host(out), ref)
+
+
+def test_x_stat_strided_rows(gpu):
+    import torch
+    X = wl.make_tokens(wl.CONFIGS["cfg1_small"], 0)
+    big = torch.zeros((256, 640), dtype=torch.float16, device=gpu)
+    big[:, :512] = dev(X, gpu)
+    out = empty((512,), torch.float32, gpu)
+    tlq.x_stat(big[:, :512], tlq.params(), out)
+    assert np.array_equal(host(out), orc.x_stat_mean(X))
+
+
+# ----------------------------------------------------------- S1 scale table
+def test_scale_table_matches_oracle(gpu):
+    import torch
+    rng = np.random.default_rng(5)
+    xs = np.concatenate([rng.lognormal(0, 1.5, 4000), [0.0, 1e-9, 1.0, 2.0 ** -14, 65504.0]]).astype(np.float32)
+    al = wl.alpha_grid(20)
+    out = empty((20, xs.size), torch.float32, gpu)
+    tlq.scale_table(dev(xs, gpu), dev(al, gpu), out)
+    got, ref = host(out), orc.scale_table(xs, al)
+    assert np.all(got[0] == 1.0)                       # alpha = 0 -> unit scales exactly
+    ulp = np.abs(got.view(np.int32).astype(np.int64) - ref.view(np.int32).astype(np.int64))
+    assert ulp.max() <= 1, "device pow differs from libm by more than one float ulp"
+    print(f"scale table: {int((ulp > 0).sum())} of {ulp.size} entries differ by one ulp")
+    assert (ulp > 0).mean() < 1e-4
+
+
+# ------------------------------------------------------------ S2 fake quant
+@pytest.mark.parametrize("bits,group,co,ci,sym", [
+    (4, 128, 512, 512, 0), (3, 128, 300, 1408, 0), (8, 128, 64, 1024, 0), (4, 32, 100, 544, 0),
+    (4, 64, 37, 11008, 0), (2, 8, 50, 72, 0), (4, 512, 64, 1024, 0), (4, 0, 70, 1000, 0),
+    (4, 1024, 33, 2048, 0), (3, 24, 19, 240, 0), (4, 0, 64, 4096, 1), (8, 128, 64, 512, 1),
+    (4, 200, 16, 1000, 1),
+])
+def test_fake_quant_bit_exact(gpu, bits, group, co, ci, sym):
+    rng = np.random.default_rng(bits * 1000 + group + co)
+    W = (rng.standard_normal((co, ci)) * 0.02).astype(np.float16)
+    s = rng.lognormal(0, 0.7, ci).astype(np.float32)
+    for bf16 in (False, True):
+        Wv = as_bf16_values(W) if bf16 else W
+        p = tlq.params(bits=bits, group=group, symmetric=sym, x_dtype=tlq.BF16 if bf16 else tlq.F16)
+        for sv in (s, None):
+            codes, zp, delta, wdq = run_fake_quant(Wv, sv, p, gpu, bf16)
+            rc, rz, rd, rq = orc.fake_quant(Wv, sv, bits, group, symmetric=bool(sym))
+            assert np.array_equal(codes, rc)
+            assert np.array_equal(zp, rz)
+            assert np.array_equal(delta.view(np.uint32), rd.view(np.uint32))
+            exp = orc.round_to_bf16(rq) if bf16 else rq.astype(np.float16).astype(np.float32)
+            assert np.array_equal(wdq.astype(np.float32), exp)
+
+
+def test_fake_quant_adversarial_groups(gpu):
+    # constant groups, one-sided groups, exact .5 ties, tiny and huge magnitudes, zeros
+    rows = []
+    rows.append(np.full(128, 0.5))
+    rows.append(np.zeros(128))
+    rows.append(np.linspace(1.0, 2.0, 128))            # all positive: zero point saturates
+    rows.append(-np.linspace(1.0, 2.0, 128))           # all negative
+    rows.append(np.concatenate([[-7.5, 7.5], np.arange(-7.0, 7.0, 14.0 / 126)]))
+    rows.append(np.concatenate([[0.0, 15.0], np.arange(126) % 16 + 0.5]))   # ties at .5, delta = 1
+    rows.append(np.full(128, 6e-8))                    # fp16 subnormal
+    rows.append(np.concatenate([[-60000.0, 60000.0], np.zeros(126)]))
+    W = np.stack(rows).astype(np.float16)
+    W = np.concatenate([W, W[:, ::-1]], axis=1)         # two groups per row
+    for bits in (3, 4):
+        for s in (None, np.exp2(np.random.default_rng(0).integers(-3, 4, 256)).astype(np.float32)):
+            p = tlq.params(bits=bits, group=128)
+            codes, zp, delta, wdq = run_fake_quant(W, s, p, gpu)
+            rc, rz, rd, rq = orc.fake_quant(W, s, bits, 128)
+            assert np.array_equal(codes, rc) and np.array_equal(zp, rz)
+            assert np.array_equal(delta.view(np.uint32), rd.view(np.uint32))
+            with np.errstate(over="ignore"):
+                assert np.array_equal(wdq, rq.astype(np.float16))
+
+
+# ------------------------------------------------ f_fp output (store epilogue)
+@pytest.mark.parametrize("n,ci,co", [(256, 512, 512), (300, 200, 203), (1, 8, 1), (700, 1096, 520)])
+def test_ref_output(gpu, n, ci, co):
+    import torch
+    rng = np.random.default_rng(n * 7 + co)
+    X = rng.standard_normal((n, ci)).astype(np.float16)
+    W = (rng.standard_normal((co, ci)) * 0.05).astype(np.float16)
+    ld = (co + 7) // 8 * 8
+    for bf16 in (False, True):
+        Xv, Wv = (as_bf16_values(X), as_bf16_values(W)) if bf16 else (X, W)
+        ref = orc.ref_output(Xv, Wv)
+        scale = np.abs(Xv.astype(np.float64)) @ np.abs(Wv.astype(np.float64)).T
+        for ydt, tdt in ((tlq.F32, torch.float32), (tlq.F16, torch.float16), (tlq.BF16, torch.bfloat16)):
+            p = tlq.params(x_dtype=tlq.BF16 if bf16 else tlq.F16, yref_dtype=ydt)
+            Yfull = torch.full((n, ld), 7.0, dtype=tdt, device=gpu)
+            tlq.ref_output(dev(Xv, gpu, bf16), dev(Wv, gpu, bf16), Yfull[:, :co], p)
+            got = host(Yfull).astype(np.float64)
+            assert np.all(got[:, co:] == 7.0)           # padding columns untouched
+            eps = {tlq.F32: 2.0 ** -24, tlq.F16: 2.0 ** -11, tlq.BF16: 2.0 ** -8}[ydt]
+            tol = 1e-6 * scale + eps * np.abs(ref) * 1.01 + 1e-7
+            assert np.all(np.abs(got[:, :co] - ref) <= tol)
+
+
+# --------------------------------------------------------- S3 + S4 single call
+@pytest.mark.parametrize("n,ci,co,ydt", [(256, 512, 512, tlq.F16), (300, 200, 203, tlq.F32),
+                                         (1000, 1024, 777, tlq.F16), (5, 64, 9, tlq.BF16)])
+def test_weighted_layer_err(gpu, n, ci, co, ydt):
+    import torch
+    rng = np.random.default_rng(n + ci + co)
+    X = rng.standard_normal((n, ci)).astype(np.float16)
+    W = (rng.standard_normal((co, ci)) * 0.03).astype(np.float16)
+    w = rng.uniform(0.1, 2.0, n).astype(np.float32)
+    s = np.exp2(rng.integers(-2, 3, ci)).astype(np.float32)       # exact reciprocals
+    _, _, _, deq = orc.fake_quant(W, s, 4, 8)
+    wdq = deq.astype(np.float16)
+    Yd = orc.ref_output(X, W)
+    if ydt == tlq.F32:
+        Y, tY = Yd.astype(np.float32), dev(Yd.astype(np.float32), gpu)
+    elif ydt == tlq.F16:
+        Y, tY = Yd.astype(np.float16), dev(Yd.astype(np.float16), gpu)
+    else:
+        Y = as_bf16_values(Yd)
+        tY = dev(Y, gpu, bf16=True)
+    if co % 8:
+        pad = torch.zeros((n, (co + 7) // 8 * 8), dtype=tY.dtype, device=gpu)
+        pad[:, :co] = tY
+        tY = pad[:, :co]
+    p = tlq.params(group=8, yref_dtype=ydt)
+    for inv in (None, (1.0 / s).astype(np.float32)):
+        loss = empty((1,), torch.float32, gpu)
+        pte = empty((n,), torch.float32, gpu)
+        tlq.weighted_layer_err(dev(X, gpu), dev(wdq, gpu), None if inv is None else dev(inv, gpu), tY,
+                               dev(w, gpu), p, loss, pte)
+        L, e = orc.weighted_layer_err(X, wdq, Y, w, inv_s=inv)
+        assert abs(host(loss)[0] - L) / L < LOSS_RTOL
+        np.testing.assert_allclose(host(pte), e, rtol=LOSS_RTOL)
+        # without the per-token output the loss must be bit-identical
+        loss2 = empty((1,), torch.float32, gpu)
+        tlq.weighted_layer_err(dev(X, gpu), dev(wdq, gpu), None if inv is None else dev(inv, gpu), tY,
+                               dev(w, gpu), p, loss2)
+        assert host(loss2)[0] == host(loss)[0]
+
+
+# -------------------------------------------------------------- the search
+def _search_inputs(X, W, w, ydt=tlq.F16):
+    Yd = orc.ref_output(X, W)
+    if ydt == tlq.F32:
+        return Yd.astype(np.float32)
+    return Yd.astype(np.float16)
+
+
+def run_search(gpu, X, W, Y, w, al, p, bf16=False, x_stat_in=None):
+    import torch
+    n, ci = X.shape
+    co = W.shape[0]
+    na = al.size
+    best = empty((ci,), torch.float32, gpu)
+    idx = empty((1,), torch.int32, gpu)
+    losses = empty((na,), torch.float32, gpu)
+    st = empty((na, ci), torch.float32, gpu)
+    tY = dev(Y, gpu)
+    if co % 8:                                   # row stride must be a multiple of 8 (4 for fp32)
+        pad = torch.zeros((n, (co + 7) // 8 * 8), dtype=tY.dtype, device=gpu)
+        pad[:, :co] = tY
+        tY = pad[:, :co]
+    tlq.scale_search(dev(X, gpu, bf16), dev(W, gpu, bf16), tY, dev(w, gpu), dev(al, gpu), p, best,
+                     idx, losses, x_stat_in=None if x_stat_in is None else dev(x_stat_in, gpu),
+                     s_table_out=st)
+    torch.cuda.synchronize()
+    return host(best), int(host(idx)[0]), host(losses), host(st)
+
+
+def test_scale_search_cfg1_full_parity(gpu):
+    c = wl.CONFIGS["cfg1_small"]
+    X, W, w = wl.make_tokens(c, 0), wl.make_weight(c, 0), wl.make_token_weights(c, 0)
+    al = wl.alpha_grid(c.n_alpha)
+    for ydt in (tlq.F16, tlq.F32):
+        Y = _search_inputs(X, W, w, ydt)
+        p = tlq.params(bits=c.bits, group=c.group, yref_dtype=ydt)
+        best, idx, losses, st = run_search(gpu, X, W, Y, w, al, p)
+        ref = orc.scale_search(X, W, Y, w, c.bits, c.group, al)
+        assert np.array_equal(st, ref["s_table"]), "scale table differs from the oracle"
+        worst = check_losses(losses, ref["losses"], idx, "cfg1")
+        print(f"cfg1 ydt={ydt}: max rel loss error {worst:.2e}, best {idx} (oracle {ref['best_idx']})")
+        assert np.array_equal(best, st[idx])
+        assert idx == int(np.argmin(losses))
+        # determinism: fixed-order reductions, no float atomics
+        best2, idx2, losses2, _ = run_search(gpu, X, W, Y, w, al, p)
+        assert idx2 == idx and np.array_equal(losses2.view(np.uint32), losses.view(np.uint32))
+
+
+def test_scale_search_alpha0_equals_two_step_path(gpu):
+    import torch
+    c = wl.CONFIGS["cfg1_small"]
+    X, W, w = wl.make_tokens(c, 0), wl.make_weight(c, 0), wl.make_token_weights(c, 0)
+    Y = _search_inputs(X, W, w)
+    p = tlq.params(bits=4, group=128)
+    _, _, losses, st = run_search(gpu, X, W, Y, w, wl.alpha_grid(20), p)
+    tW = dev(W, gpu)
+    for k in (0, 9):
+        wdq = torch.empty_like(tW)
+        tlq.fake_quant(tW, dev(st[k], gpu), p, Wdq=wdq)
+        loss = empty((1,), torch.float32, gpu)
+        inv = (1.0 / st[k].astype(np.float64)).astype(np.float32)
+        tlq.weighted_layer_err(dev(X, gpu), wdq, dev(inv, gpu), dev(Y, gpu), dev(w, gpu), p, loss)
+        # the two-step path rounds deq to 16 bits before folding 1/s: tiny difference allowed
+        assert abs(host(loss)[0] - losses[k]) / losses[k] < 1e-4
+        if k == 0:
+            assert host(loss)[0] == losses[0]      # s = 1: identical operands, identical order
+
+
+@pytest.mark.parametrize("n,ci,co,bits,group,bf16", [
+    (1000, 1024, 777, 4, 128, False), (515, 384, 300, 3, 128, False), (640, 1408, 512, 4, 64, True),
+    (300, 256, 1030, 4, 0, False),
+])
+def test_scale_search_ragged_multi_tile(gpu, n, ci, co, bits, group, bf16):
+    rng = np.random.default_rng(n + ci)
+    X = rng.standard_normal((n, ci)).astype(np.float32)
+    oc = rng.choice(ci, max(1, ci // 100), replace=False)
+    X[n // 2:, oc] *= 25.0
+    W = (rng.standard_normal((co, ci)) * 0.02).astype(np.float32)
+    w = rng.lognormal(0, 1, n)
+    w = (w / w.sum()).astype(np.float32)
+    if bf16:
+        X, W = as_bf16_values(X), as_bf16_values(W)
+    else:
+        X, W = X.astype(np.float16), W.astype(np.float16)
+    Y = orc.ref_output(X, W).astype(np.float32)
+    al = wl.alpha_grid(10)
+    p = tlq.params(bits=bits, group=group, x_dtype=tlq.BF16 if bf16 else tlq.F16, yref_dtype=tlq.F32)
+    best, idx, losses, st = run_search(gpu, X, W, Y, w, al, p, bf16=bf16)
+    ref = orc.scale_search(X, W, Y, w, bits, group, al)
+    ulp = np.abs(st.view(np.int32).astype(np.int64) - ref["s_table"].view(np.int32))
+    assert ulp.max() <= 1
+    worst = check_losses(losses, ref["losses"], idx, f"{n}x{ci}x{co}")
+    print(f"{n}x{ci}x{co} w{bits} g{group} bf16={bf16}: max rel loss error {worst:.2e}")
+    assert np.array_equal(best, st[idx])
+
+
+def test_scale_search_with_supplied_x_stat_and_nonfinite(gpu):
+    c = wl.CONFIGS["cfg1_small"]
+    X, W, w = wl.make_tokens(c, 0), wl.make_weight(c, 0), wl.make_token_weights(c, 0)
+    Y = _search_inputs(X, W, w)
+    al = wl.alpha_grid(6)
+    p = tlq.params(bits=4, group=128)
+    xs = orc.x_stat_max(X)                      # a different statistic, passed in explicitly
+    best, idx, losses, st = run_search(gpu, X, W, Y, w, al, p, x_stat_in=xs)
+    ref = orc.scale_search(X, W, Y, w, 4, 128, al, x_stat=xs)
+    assert np.array_equal(st, ref["s_table"])
+    check_losses(losses, ref["losses"], idx, "x_max")
+    # a non-finite reference output makes every loss non-finite: +inf, index -1
+    Ybad = Y.copy()
+    Ybad[3, 7] = np.float16(np.inf)
+    best, idx, losses, st = run_search(gpu, X, W, Ybad, w, al, p)
+    assert idx == -1 and np.all(np.isposinf(losses)) and np.all(np.isnan(best))
+
+
+# ------------------------------------------------------------ S6 apply_best
+@pytest.mark.parametrize("n,ci,co,bits,bf16", [(256, 512, 512, 4, False), (300, 384, 200, 3, True)])
+def test_apply_best(gpu, n, ci, co, bits, bf16):
+    import torch
+    rng = np.random.default_rng(co)
+    X = rng.standard_normal((n, ci)).astype(np.float16)
+    W = (rng.standard_normal((co, ci)) * 0.02).astype(np.float16)
+    if bf16:
+        X, W = as_bf16_values(X), as_bf16_values(W)
+    s = rng.lognormal(0, 0.5, ci).astype(np.float32)
+    p = tlq.params(bits=bits, group=128, x_dtype=tlq.BF16 if bf16 else tlq.F16)
+    out = empty((n, co), torch.bfloat16 if bf16 else torch.float16, gpu)
+    tlq.apply_best(dev(X, gpu, bf16), dev(W, gpu, bf16), dev(s, gpu), p, out)
+    ref = orc.apply_best(X, W, s, bits, 128)
+    got = host(out).astype(np.float64)
+    eps = 2.0 ** -8 if bf16 else 2.0 ** -11
+    # operand rounding (one 16-bit rounding of deq/s) plus the output rounding
+    _, _, _, deq = orc.fake_quant(W, s, bits, 128)
+    mag = np.abs(X.astype(np.float64) / s) @ np.abs(deq.astype(np.float64)).T
+    assert np.all(np.abs(got - ref) <= eps * mag * 0.6 + eps * np.abs(ref) * 1.01 + 1e-6)
+
+
+# --------------------------------------- full size, the benchmark's launch shape
+def test_full_size_7b_linear_sampled_parity(gpu):
+    """o_proj-shaped linear of the 7B workload (10240 tokens, 4096x4096, 20
+    candidates), exactly as the benchmark launches it.  The oracle evaluates
+    three candidates in full and 64 sampled tokens for every candidate."""
+    import torch
+    c = wl.CONFIGS["cfg2_7b_w4"]
+    li = 3
+    X, W, w = wl.make_tokens(c, li), wl.make_weight(c, li), wl.make_token_weights(c, li)
+    Y = orc.ref_output(X, W).astype(np.float16)
+    al = wl.alpha_grid(c.n_alpha)
+    p = tlq.params(bits=c.bits, group=c.group)
+    best, idx, losses, st = run_search(gpu, X, W, Y, w, al, p)
+    ost = orc.scale_table(orc.x_stat_mean(X), al)      # the oracle's own table feeds the oracle
+    ulp = np.abs(st.view(np.int32).astype(np.int64) - ost.view(np.int32))
+    assert ulp.max() <= 1
+    print(f"7B o_proj: {int((ulp > 0).sum())} scale-table entries off by one ulp; best alpha index {idx}")
+    # (a) full oracle on three candidates, including the selected one
+    for k in sorted({0, idx, 19}):
+        _, _, _, deq = orc.fake_quant(W, ost[k], c.bits, c.group)
+        L, e = orc.weighted_layer_err(X, deq, Y, w, s=ost[k])
+        rel = abs(losses[k] - L) / L
+        print(f"  candidate {k}: gpu {losses[k]:.6e} oracle {L:.6e} rel {rel:.2e}")
+        assert rel < LOSS_RTOL
+    # (b) every candidate on 64 sampled tokens through the single-candidate entry point
+    rows = np.sort(np.random.default_rng(1).choice(X.shape[0], 64, replace=False))
+    tX, tW, tY, tw = dev(X, gpu), dev(W, gpu), dev(Y, gpu), dev(w, gpu)
+    wdq = torch.empty_like(tW)
+    loss = empty((1,), torch.float32, gpu)
+    pte = empty((X.shape[0],), torch.float32, gpu)
+    for k in range(0, 20, 3):
+        tlq.fake_quant(tW, dev(ost[k], gpu), p, Wdq=wdq)
+        inv = (1.0 / ost[k].astype(np.float64)).astype(np.float32)
+        tlq.weighted_layer_err(tX, wdq, dev(inv, gpu), tY, tw, p, loss, pte)
+        _, _, _, deq = orc.fake_quant(W, ost[k], c.bits, c.group)
+        e = orc.per_token_err(Y[rows], orc.quantised_output(X[rows], deq.astype(np.float16), inv_s=inv))
+        np.testing.assert_allclose(host(pte)[rows], e, rtol=LOSS_RTOL)
+        assert abs(host(loss)[0] - losses[k]) / losses[k] < 1e-4
+    # the losses are a proper objective: all finite and positive, minimum at idx
+    assert np.all(np.isfinite(losses)) and np.all(losses > 0) and idx == int(np.argmin(losses))
