@@ -60,6 +60,8 @@ def build(verbose: bool = True, extra=()) -> str:
     r = subprocess.run(cmd, capture_output=True, text=True)
     if r.returncode != 0:
         raise RuntimeError("link failed:\n" + r.stdout + r.stderr)
+    import ctypes
+    ctypes.CDLL(LIB)  # an unresolved symbol must fail the build, not the first caller
     if verbose:
         print("built", LIB)
     return LIB

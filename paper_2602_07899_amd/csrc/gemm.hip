@@ -290,8 +290,275 @@ __global__ __launch_bounds__((BO / WO) * (BT / WT) * 64) void gemm_kernel(GemmDe
   }
 }
 
+
+// ---------------------------------------------------------------------------
+// Pipelined variant for c_in % BK == 0 (every group-128 workload).
+//
+// Global -> LDS goes through the buffer-load-to-LDS path (no VGPR staging, no
+// LDS store instructions): each wave-wide load drops 64 x 16 B contiguously at
+// an LDS base held in M0, so the XOR swizzle is applied on the *global* side
+// (lane l fetches the chunk that belongs in LDS slot l).  Rows past the edge
+// of the matrix fall outside the buffer descriptor's range and arrive as
+// zeros.  NSTAGE k-tiles form a ring; the refill of a slot is issued as soon
+// as the block-wide barrier shows that every wave has finished reading it, so
+// NSTAGE-1 k-tiles of loads are always in flight.
+//
+// The compiler cannot see that fragment reads and LDS-DMA writes touch
+// different ring slots and would drain the load counter before every LDS read,
+// so the fragment reads are issued from inline assembly and the waits on the
+// two counters are placed by hand:
+//   - "lgkmcnt(0)" ties the fragment registers, so no MFMA can be scheduled
+//     before its operands have arrived;
+//   - "vmcnt(n)" before the barrier waits for this wave's share of the next
+//     k-tile only.
+typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
+typedef __attribute__((address_space(3))) void* lds_ptr_t;
+
+template <int IMM>
+__device__ __forceinline__ void lds_read128(u32x4& v, uint32_t addr) {
+  asm volatile("ds_read_b128 %0, %1 offset:%2" : "=v"(v) : "v"(addr), "n"(IMM));
+}
+// Wait for every outstanding LDS read; the fragments are tied through the
+// statement so that nothing consuming them can be scheduled above it.
+__device__ __forceinline__ void lds_wait6(u32x4& f0, u32x4& f1, u32x4& f2, u32x4& f3, u32x4& f4,
+                                          u32x4& f5) {
+  asm volatile("s_waitcnt lgkmcnt(0)"
+               : "+v"(f0), "+v"(f1), "+v"(f2), "+v"(f3), "+v"(f4), "+v"(f5)
+               :
+               : "memory");
+}
+template <int N>
+__device__ __forceinline__ void wait_vmcnt() {
+  asm volatile("s_waitcnt vmcnt(%0)" ::"n"(N) : "memory");
+}
+
+template <typename T, int BK_, int NSTAGE, int EPI>
+__global__ __launch_bounds__(512) void gemm_dma_kernel(GemmDev a) {
+#if defined(__HIP_DEVICE_COMPILE__)  // the body uses gfx950 builtins the host pass cannot parse
+  constexpr int BO = 256, BT = 256, WO = 128, WT = 64, NWO = 2, NW = 8, NT = 512;
+  constexpr int FA = WO / 32, FB = WT / 32, KK = BK_ / 16;
+  constexpr int RB = BK_ * 2;             // bytes per LDS row
+  constexpr int CPR = BK_ / 8;            // 16-byte chunks per row
+  constexpr int STAGE = (BO + BT) * RB;
+  constexpr int RPD = 64 / CPR;           // rows covered by one wave-wide load
+  constexpr int DPO = BO / RPD / NW;      // loads per wave per operand per k-tile
+  constexpr int LPS = 2 * DPO;            // loads per wave per k-tile
+  static_assert(KK % 2 == 0 && NSTAGE >= 2 && (NSTAGE - 1) * LPS < 64, "pipeline shape");
+  __shared__ __attribute__((aligned(1024))) unsigned char lds[NSTAGE * STAGE];
+  __shared__ float red[NW];
+
+  const int64_t bid = blockIdx.x;
+  const int64_t round = bid / (8 * PATCH_O * PATCH_T);
+  const int within = (int)(bid % (8 * PATCH_O * PATCH_T));
+  const int64_t patch = round * 8 + (within & 7);
+  const int slot = within >> 3;
+  if (patch >= a.n_patches) return;
+  const int ppc = a.npo * a.npt;
+  const int cand = (int)(patch / ppc);
+  const int prem = (int)(patch % ppc);
+  const int to = (prem / a.npt) * PATCH_O + (slot % PATCH_O);
+  const int tt = (prem % a.npt) * PATCH_T + (slot / PATCH_O);
+  if (to >= a.tiles_o || tt >= a.tiles_t) return;
+  const int64_t o0 = (int64_t)to * BO, t0 = (int64_t)tt * BT;
+
+  const int tid = threadIdx.x, lane = tid & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const int wo = wave % NWO, wt = wave / NWO;
+
+  // buffer descriptors over the valid rows of this block's two operand panels
+  const int64_t vro = (a.c_out - o0) < BO ? (a.c_out - o0) : BO;
+  const int64_t vrt = (a.n_tok - t0) < BT ? (a.n_tok - t0) : BT;
+  const uint16_t* pA = a.Wh + (int64_t)cand * a.w_cand_stride + o0 * a.ldw;
+  const uint16_t* pB = a.X + t0 * a.ldx;
+  const __amdgpu_buffer_rsrc_t rA = __builtin_amdgcn_make_buffer_rsrc(
+      (void*)pA, 0, (int)(((vro - 1) * a.ldw + a.c_in) * 2), 0x00020000);
+  const __amdgpu_buffer_rsrc_t rB = __builtin_amdgcn_make_buffer_rsrc(
+      (void*)pB, 0, (int)(((vrt - 1) * a.ldx + a.c_in) * 2), 0x00020000);
+
+  // per-lane global byte offsets of the chunks this lane fetches
+  int voa[DPO], vob[DPO];
+#pragma unroll
+  for (int j = 0; j < DPO; ++j) {
+    const int r = (j * NW + wave) * RPD + lane / CPR;
+    const int p = lane % CPR;
+    const int c = BK_ == 64 ? (p ^ ((r >> 1) & 7)) : (p ^ ((r >> 2) & 3));
+    voa[j] = r * (int)a.ldw * 2 + c * 16;
+    vob[j] = r * (int)a.ldx * 2 + c * 16;
+  }
+  auto issue = [&](int64_t kt) {
+    const int st = (int)(kt % NSTAGE);
+    const int so = (int)(kt * BK_ * 2);
+    unsigned char* sb = lds + st * STAGE;
+#pragma unroll
+    for (int j = 0; j < DPO; ++j) {
+      __builtin_amdgcn_raw_ptr_buffer_load_lds(rA, (lds_ptr_t)(sb + (j * NW + wave) * 1024), 16,
+                                               voa[j], so, 0, 0);
+      __builtin_amdgcn_raw_ptr_buffer_load_lds(rB, (lds_ptr_t)(sb + BO * RB + (j * NW + wave) * 1024),
+                                               16, vob[j], so, 0, 0);
+    }
+  };
+
+  // fragment read addresses (bytes from the start of a stage)
+  const int frow = lane & 31, fhi = lane >> 5;
+  const uint32_t lds0 = (uint32_t)(uintptr_t)(lds_ptr_t)lds;
+  uint32_t offA[KK], offB[KK];
+#pragma unroll
+  for (int kk = 0; kk < KK; ++kk) {
+    const int c = kk * 2 + fhi;
+    const int p = BK_ == 64 ? (c ^ ((frow >> 1) & 7)) : (c ^ ((frow >> 2) & 3));
+    const uint32_t o = (uint32_t)(frow * RB + p * 16);
+    offA[kk] = lds0 + o + (wo * WO) * RB;
+    offB[kk] = lds0 + o + BO * RB + (wt * WT) * RB;
+  }
+  u32x4 F[2][FA + FB];
+  auto fread = [&](int buf, int stage, int kk) {
+    const uint32_t sa = offA[kk] + stage * STAGE, sb2 = offB[kk] + stage * STAGE;
+    lds_read128<0 * 32 * RB>(F[buf][0], sa);
+    lds_read128<1 * 32 * RB>(F[buf][1], sa);
+    lds_read128<2 * 32 * RB>(F[buf][2], sa);
+    lds_read128<3 * 32 * RB>(F[buf][3], sa);
+    lds_read128<0 * 32 * RB>(F[buf][4], sb2);
+    lds_read128<1 * 32 * RB>(F[buf][5], sb2);
+  };
+  auto fwait = [&](int buf) {
+    lds_wait6(F[buf][0], F[buf][1], F[buf][2], F[buf][3], F[buf][4], F[buf][5]);
+  };
+
+  f32x16 acc[FA][FB];
+#pragma unroll
+  for (int i = 0; i < FA; ++i)
+#pragma unroll
+    for (int j = 0; j < FB; ++j)
+#pragma unroll
+      for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.0f;
+  auto mma = [&](int buf) {
+#pragma unroll
+    for (int i = 0; i < FA; ++i)
+#pragma unroll
+      for (int j = 0; j < FB; ++j)
+        acc[i][j] = Mma<T>::run(__builtin_bit_cast(uint4, F[buf][i]),
+                                __builtin_bit_cast(uint4, F[buf][FA + j]), acc[i][j]);
+  };
+
+  const int64_t nk = a.c_in / BK_;
+  // prologue: fill the whole ring, wait for k-tile 0
+#pragma unroll
+  for (int s = 0; s < NSTAGE; ++s) issue(s);
+  wait_vmcnt<(NSTAGE - 1) * LPS>();
+  __builtin_amdgcn_s_barrier();
+  fread(0, 0, 0);
+  fwait(0);
+  for (int64_t kt = 0; kt < nk; ++kt) {
+    const int st = (int)(kt % NSTAGE);
+#pragma unroll
+    for (int kk = 0; kk < KK - 1; ++kk) {
+      fread((kk + 1) & 1, st, kk + 1);
+      __builtin_amdgcn_sched_barrier(0);
+      mma(kk & 1);
+      __builtin_amdgcn_sched_barrier(0);
+      fwait((kk + 1) & 1);
+    }
+    // every fragment of k-tile kt is in registers: release its slot, take the next tile
+    wait_vmcnt<(NSTAGE - 2) * LPS>();
+    __builtin_amdgcn_s_barrier();
+    __builtin_amdgcn_sched_barrier(0);
+    issue(kt + NSTAGE);
+    fread(0, (int)((kt + 1) % NSTAGE), 0);
+    __builtin_amdgcn_sched_barrier(0);
+    mma((KK - 1) & 1);
+    __builtin_amdgcn_sched_barrier(0);
+    fwait(0);
+  }
+  wait_vmcnt<0>();
+  __syncthreads();
+
+  // ---- epilogue (same as gemm_kernel)
+  if (EPI == EPI_STORE) {
+#pragma unroll
+    for (int j = 0; j < FB; ++j) {
+      const int64_t t = t0 + wt * WT + j * 32 + frow;
+      if (t >= a.n_tok) continue;
+#pragma unroll
+      for (int i = 0; i < FA; ++i)
+#pragma unroll
+        for (int q = 0; q < 4; ++q) {
+          const int64_t o = o0 + wo * WO + i * 32 + q * 8 + fhi * 4;
+          float y[4] = {acc[i][j][q * 4], acc[i][j][q * 4 + 1], acc[i][j][q * 4 + 2], acc[i][j][q * 4 + 3]};
+          if (o + 3 < a.c_out) store_y4(a.Yout, a.odt, t * a.ldo + o, y);
+          else
+            for (int r = 0; r < 4; ++r)
+              if (o + r < a.c_out) store_y1(a.Yout, a.odt, t * a.ldo + o + r, y[r]);
+        }
+    }
+    return;
+  }
+  float part = 0.0f;
+  float* rows = reinterpret_cast<float*>(lds);
+#pragma unroll
+  for (int j = 0; j < FB; ++j) {
+    const int64_t t = t0 + wt * WT + j * 32 + frow;
+    const bool tok = t < a.n_tok;
+    float sumsq = 0.0f;
+    if (tok) {
+#pragma unroll
+      for (int i = 0; i < FA; ++i)
+#pragma unroll
+        for (int q = 0; q < 4; ++q) {
+          const int64_t o = o0 + wo * WO + i * 32 + q * 8 + fhi * 4;
+          if (o + 3 < a.c_out) {
+            float y[4];
+            load_y4(a.Yref, a.ydt, t * a.ldy + o, y);
+#pragma unroll
+            for (int r = 0; r < 4; ++r) {
+              const float d = y[r] - acc[i][j][q * 4 + r];
+              sumsq += d * d;
+            }
+          } else {
+            for (int r = 0; r < 4; ++r)
+              if (o + r < a.c_out) {
+                const float d = load_y(a.Yref, a.ydt, t * a.ldy + o + r) - acc[i][j][q * 4 + r];
+                sumsq += d * d;
+              }
+          }
+        }
+      part += a.token_w[t] * sumsq;
+    }
+    if (EPI == EPI_LOSS_TOK) {
+      const float both = sumsq + __shfl_xor(sumsq, 32, 64);
+      if (fhi == 0) rows[wo * BT + wt * WT + j * 32 + frow] = both;
+    }
+  }
+#pragma unroll
+  for (int off = 32; off >= 1; off >>= 1) part += __shfl_xor(part, off, 64);
+  if (lane == 0) red[wave] = part;
+  __syncthreads();
+  if (tid == 0) {
+    float s = 0.0f;
+#pragma unroll
+    for (int w = 0; w < NW; ++w) s += red[w];
+    a.partial[((int64_t)cand * a.tiles_o + to) * a.tiles_t + tt] = s;
+  }
+  if (EPI == EPI_LOSS_TOK) {
+    for (int i = tid; i < BT; i += NT) {
+      const int64_t t = t0 + i;
+      if (t < a.n_tok) {
+        float s = 0.0f;
+#pragma unroll
+        for (int w = 0; w < NWO; ++w) s += rows[w * BT + i];
+        a.tok_partial[(int64_t)to * a.n_tok + t] = s;
+      }
+    }
+  }
+#endif
+}
+
 // ---- host side ---------------------------------------------------------------
 constexpr int kBO = 256, kBT = 256, kWO = 128, kWT = 64;
+#ifndef TLQ_DMA_BK
+#define TLQ_DMA_BK 32
+#define TLQ_DMA_STAGES 4
+#endif
+constexpr int kDmaBK = TLQ_DMA_BK, kDmaStages = TLQ_DMA_STAGES;
 
 void gemm_tile_counts(int64_t n_tok, int64_t c_out, int64_t* tiles_o, int64_t* tiles_t) {
   *tiles_o = ceil_div(c_out, kBO);
@@ -322,8 +589,15 @@ static hipError_t launch_gemm(const GemmArgs& g, const char* name, hipStream_t s
   if (blocks > 0x7fffffffLL) return hipErrorInvalidValue;
   ProfScope ps(name, stream, 2.0 * (double)g.n_tok * (double)g.c_in * (double)g.c_out * g.n_cand);
   constexpr int NT = (kBO / kWO) * (kBT / kWT) * 64;
-  if (!g.bf16) gemm_kernel<F16, kBO, kBT, kWO, kWT, EPI><<<(unsigned)blocks, NT, 0, stream>>>(d);
-  else gemm_kernel<BF16, kBO, kBT, kWO, kWT, EPI><<<(unsigned)blocks, NT, 0, stream>>>(d);
+  // the pipelined kernel needs whole k-tiles and 32-bit byte offsets inside a 256-row panel
+  const bool dma = (g.c_in % kDmaBK) == 0 && g.ldw < (1 << 21) && g.ldx < (1 << 21);
+  if (dma) {
+    if (!g.bf16) gemm_dma_kernel<F16, kDmaBK, kDmaStages, EPI><<<(unsigned)blocks, NT, 0, stream>>>(d);
+    else gemm_dma_kernel<BF16, kDmaBK, kDmaStages, EPI><<<(unsigned)blocks, NT, 0, stream>>>(d);
+  } else {
+    if (!g.bf16) gemm_kernel<F16, kBO, kBT, kWO, kWT, EPI><<<(unsigned)blocks, NT, 0, stream>>>(d);
+    else gemm_kernel<BF16, kBO, kBT, kWO, kWT, EPI><<<(unsigned)blocks, NT, 0, stream>>>(d);
+  }
   return hipGetLastError();
 }
 
