@@ -20,6 +20,8 @@
 // the fragment reads and for the tile writes alike.
 // Two LDS stages: the global loads of k-tile i+1 are issued before the MFMAs of
 // k-tile i and written to the other stage afterwards; one barrier per k-tile.
+#include <utility>
+
 #include "common.h"
 
 namespace tlq {
@@ -327,16 +329,36 @@ __device__ __forceinline__ void lds_wait6(u32x4& f0, u32x4& f1, u32x4& f2, u32x4
                :
                : "memory");
 }
+__device__ __forceinline__ void lds_wait8(u32x4& f0, u32x4& f1, u32x4& f2, u32x4& f3, u32x4& f4,
+                                          u32x4& f5, u32x4& f6, u32x4& f7) {
+  asm volatile("s_waitcnt lgkmcnt(0)"
+               : "+v"(f0), "+v"(f1), "+v"(f2), "+v"(f3), "+v"(f4), "+v"(f5), "+v"(f6), "+v"(f7)
+               :
+               : "memory");
+}
+// F[I] <- 16 bytes at addr + I * STEP for I = 0..N-1 (offsets must be immediates)
+template <int STEP, int... I>
+__device__ __forceinline__ void lds_read_seq(u32x4* F, uint32_t addr, std::integer_sequence<int, I...>) {
+  (lds_read128<I * STEP>(F[I], addr), ...);
+}
+template <int I, int N, typename Fn>
+__device__ __forceinline__ void static_for(Fn&& f) {
+  if constexpr (I < N) {
+    f(std::integral_constant<int, I>{});
+    static_for<I + 1, N>(f);
+  }
+}
 template <int N>
 __device__ __forceinline__ void wait_vmcnt() {
   asm volatile("s_waitcnt vmcnt(%0)" ::"n"(N) : "memory");
 }
 
-template <typename T, int BK_, int NSTAGE, int EPI>
-__global__ __launch_bounds__(512) void gemm_dma_kernel(GemmDev a) {
+template <typename T, int BK_, int NSTAGE, int NWO, int NWT, int EPI>
+__global__ __launch_bounds__(NWO * NWT * 64) void gemm_dma_kernel(GemmDev a) {
 #if defined(__HIP_DEVICE_COMPILE__)  // the body uses gfx950 builtins the host pass cannot parse
-  constexpr int BO = 256, BT = 256, WO = 128, WT = 64, NWO = 2, NW = 8, NT = 512;
-  constexpr int FA = WO / 32, FB = WT / 32, KK = BK_ / 16;
+  constexpr int BO = 256, BT = 256, WO = BO / NWO, WT = BT / NWT, NW = NWO * NWT, NT = NW * 64;
+  constexpr int FA = WO / 32, FB = WT / 32, NF = FA + FB, KK = BK_ / 16;
+  static_assert(NF == 6 || NF == 8, "fragment count");
   constexpr int RB = BK_ * 2;             // bytes per LDS row
   constexpr int CPR = BK_ / 8;            // 16-byte chunks per row
   constexpr int STAGE = (BO + BT) * RB;
@@ -385,16 +407,24 @@ __global__ __launch_bounds__(512) void gemm_dma_kernel(GemmDev a) {
     voa[j] = r * (int)a.ldw * 2 + c * 16;
     vob[j] = r * (int)a.ldx * 2 + c * 16;
   }
+  // The scalar offset is not part of the descriptor's range check, so a k-tile
+  // past the end of the rows must not be fetched at all: its loads are still
+  // issued (the counter bookkeeping stays uniform) but with a per-lane offset
+  // that is out of range for any descriptor, which touches no memory and
+  // delivers zeros.
+  const int64_t nk = a.c_in / BK_;
+  constexpr int kOutOfRange = (int)0x80000000u;
   auto issue = [&](int64_t kt) {
     const int st = (int)(kt % NSTAGE);
-    const int so = (int)(kt * BK_ * 2);
+    const bool live = kt < nk;
+    const int so = live ? (int)(kt * BK_ * 2) : 0;
     unsigned char* sb = lds + st * STAGE;
 #pragma unroll
     for (int j = 0; j < DPO; ++j) {
       __builtin_amdgcn_raw_ptr_buffer_load_lds(rA, (lds_ptr_t)(sb + (j * NW + wave) * 1024), 16,
-                                               voa[j], so, 0, 0);
+                                               live ? voa[j] : kOutOfRange, so, 0, 0);
       __builtin_amdgcn_raw_ptr_buffer_load_lds(rB, (lds_ptr_t)(sb + BO * RB + (j * NW + wave) * 1024),
-                                               16, vob[j], so, 0, 0);
+                                               16, live ? vob[j] : kOutOfRange, so, 0, 0);
     }
   };
 
@@ -410,20 +440,7 @@ __global__ __launch_bounds__(512) void gemm_dma_kernel(GemmDev a) {
     offA[kk] = lds0 + o + (wo * WO) * RB;
     offB[kk] = lds0 + o + BO * RB + (wt * WT) * RB;
   }
-  u32x4 F[2][FA + FB];
-  auto fread = [&](int buf, int stage, int kk) {
-    const uint32_t sa = offA[kk] + stage * STAGE, sb2 = offB[kk] + stage * STAGE;
-    lds_read128<0 * 32 * RB>(F[buf][0], sa);
-    lds_read128<1 * 32 * RB>(F[buf][1], sa);
-    lds_read128<2 * 32 * RB>(F[buf][2], sa);
-    lds_read128<3 * 32 * RB>(F[buf][3], sa);
-    lds_read128<0 * 32 * RB>(F[buf][4], sb2);
-    lds_read128<1 * 32 * RB>(F[buf][5], sb2);
-  };
-  auto fwait = [&](int buf) {
-    lds_wait6(F[buf][0], F[buf][1], F[buf][2], F[buf][3], F[buf][4], F[buf][5]);
-  };
-
+  u32x4 F[2][NF];
   f32x16 acc[FA][FB];
 #pragma unroll
   for (int i = 0; i < FA; ++i)
@@ -431,43 +448,86 @@ __global__ __launch_bounds__(512) void gemm_dma_kernel(GemmDev a) {
     for (int j = 0; j < FB; ++j)
 #pragma unroll
       for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.0f;
-  auto mma = [&](int buf) {
-#pragma unroll
-    for (int i = 0; i < FA; ++i)
-#pragma unroll
-      for (int j = 0; j < FB; ++j)
-        acc[i][j] = Mma<T>::run(__builtin_bit_cast(uint4, F[buf][i]),
-                                __builtin_bit_cast(uint4, F[buf][FA + j]), acc[i][j]);
-  };
 
-  const int64_t nk = a.c_in / BK_;
-  // prologue: fill the whole ring, wait for k-tile 0
+  // Single operations, indexed at compile time so that every LDS offset is an
+  // immediate and every fragment stays in a fixed register.
+  auto read1 = [&](auto bufc, uint32_t sa, uint32_t sb2, auto rc) {
+    constexpr int buf = decltype(bufc)::value, r = decltype(rc)::value;
+    if constexpr (r < FA) lds_read128<r * 32 * RB>(F[buf][r], sa);
+    else lds_read128<(r - FA) * 32 * RB>(F[buf][r], sb2);
+  };
+  auto mma1 = [&](auto bufc, auto mc) {
+    constexpr int buf = decltype(bufc)::value, m = decltype(mc)::value, i = m / FB, j = m % FB;
+    acc[i][j] = Mma<T>::run(__builtin_bit_cast(uint4, F[buf][i]),
+                            __builtin_bit_cast(uint4, F[buf][FA + j]), acc[i][j]);
+  };
+  auto fwait = [&](auto bufc) {
+    constexpr int buf = decltype(bufc)::value;
+    if constexpr (NF == 6)
+      lds_wait6(F[buf][0], F[buf][1], F[buf][2], F[buf][3], F[buf][4], F[buf][5]);
+    else
+      lds_wait8(F[buf][0], F[buf][1], F[buf][2], F[buf][3], F[buf][4], F[buf][5], F[buf][6], F[buf][7]);
+  };
+  // One phase = the FA*FB MFMAs of one k16 step on fragment buffer CB, with the
+  // "side" operations of the phase (NR fragment reads into the other buffer,
+  // then ND LDS-DMA loads of k-tile `dkt`) slotted two at a time behind the
+  // leading MFMAs, so that neither the LDS queue nor the texture-address queue
+  // sees a burst that would hold back the in-order MFMA issue.
+  constexpr int M = FA * FB;
+  auto phase = [&](auto cbc, auto nrc, auto ndc, uint32_t sa, uint32_t sb2, int64_t dkt) {
+    constexpr int CB = decltype(cbc)::value, NR = decltype(nrc)::value, ND = decltype(ndc)::value;
+    static_assert(NR + ND <= 2 * M, "too many side operations for one phase");
+    const int dst = (int)(dkt % NSTAGE);
+    const bool live = dkt < nk;
+    const int so = live ? (int)(dkt * BK_ * 2) : 0;
+    unsigned char* sbase = lds + dst * STAGE;
+    static_for<0, M>([&](auto mc) {
+      constexpr int m = decltype(mc)::value;
+      mma1(cbc, mc);
+      static_for<2 * m, (2 * m + 2 < NR + ND ? 2 * m + 2 : NR + ND)>([&](auto sc) {
+        constexpr int sidx = decltype(sc)::value;
+        if constexpr (sidx < NR) {
+          read1(std::integral_constant<int, CB ^ 1>{}, sa, sb2, sc);
+        } else {
+          constexpr int d = sidx - NR, j = d / 2;
+          if constexpr ((d & 1) == 0)
+            __builtin_amdgcn_raw_ptr_buffer_load_lds(rA, (lds_ptr_t)(sbase + (j * NW + wave) * 1024), 16,
+                                                     live ? voa[j] : kOutOfRange, so, 0, 0);
+          else
+            __builtin_amdgcn_raw_ptr_buffer_load_lds(
+                rB, (lds_ptr_t)(sbase + BO * RB + (j * NW + wave) * 1024), 16,
+                live ? vob[j] : kOutOfRange, so, 0, 0);
+        }
+      });
+      __builtin_amdgcn_sched_barrier(0);
+    });
+  };
+  using C0 = std::integral_constant<int, 0>;
+
+  // prologue: fill the whole ring, wait for k-tile 0, fetch its first fragments
 #pragma unroll
   for (int s = 0; s < NSTAGE; ++s) issue(s);
   wait_vmcnt<(NSTAGE - 1) * LPS>();
   __builtin_amdgcn_s_barrier();
-  fread(0, 0, 0);
-  fwait(0);
+  static_for<0, NF>([&](auto rc) { read1(C0{}, offA[0], offB[0], rc); });
+  fwait(C0{});
   for (int64_t kt = 0; kt < nk; ++kt) {
-    const int st = (int)(kt % NSTAGE);
-#pragma unroll
-    for (int kk = 0; kk < KK - 1; ++kk) {
-      fread((kk + 1) & 1, st, kk + 1);
-      __builtin_amdgcn_sched_barrier(0);
-      mma(kk & 1);
-      __builtin_amdgcn_sched_barrier(0);
-      fwait((kk + 1) & 1);
-    }
-    // every fragment of k-tile kt is in registers: release its slot, take the next tile
+    const uint32_t so_cur = (uint32_t)((kt % NSTAGE) * STAGE);
+    static_for<0, KK - 1>([&](auto kc) {
+      constexpr int kk = decltype(kc)::value;
+      phase(std::integral_constant<int, kk & 1>{}, std::integral_constant<int, NF>{}, C0{},
+            offA[kk + 1] + so_cur, offB[kk + 1] + so_cur, 0);
+      fwait(std::integral_constant<int, (kk + 1) & 1>{});
+    });
+    // every fragment of k-tile kt is in registers: its slot can be refilled once all
+    // waves are here, and k-tile kt+1 has landed once this wave's share of it has
     wait_vmcnt<(NSTAGE - 2) * LPS>();
     __builtin_amdgcn_s_barrier();
     __builtin_amdgcn_sched_barrier(0);
-    issue(kt + NSTAGE);
-    fread(0, (int)((kt + 1) % NSTAGE), 0);
-    __builtin_amdgcn_sched_barrier(0);
-    mma((KK - 1) & 1);
-    __builtin_amdgcn_sched_barrier(0);
-    fwait(0);
+    const uint32_t so_next = (uint32_t)(((kt + 1) % NSTAGE) * STAGE);
+    phase(std::integral_constant<int, (KK - 1) & 1>{}, std::integral_constant<int, NF>{},
+          std::integral_constant<int, LPS>{}, offA[0] + so_next, offB[0] + so_next, kt + NSTAGE);
+    fwait(C0{});
   }
   wait_vmcnt<0>();
   __syncthreads();
@@ -555,10 +615,15 @@ __global__ __launch_bounds__(512) void gemm_dma_kernel(GemmDev a) {
 // ---- host side ---------------------------------------------------------------
 constexpr int kBO = 256, kBT = 256, kWO = 128, kWT = 64;
 #ifndef TLQ_DMA_BK
-#define TLQ_DMA_BK 32
-#define TLQ_DMA_STAGES 4
+#define TLQ_DMA_BK 64
+#define TLQ_DMA_STAGES 2
+#endif
+#ifndef TLQ_DMA_NWO
+#define TLQ_DMA_NWO 2
+#define TLQ_DMA_NWT 4
 #endif
 constexpr int kDmaBK = TLQ_DMA_BK, kDmaStages = TLQ_DMA_STAGES;
+constexpr int kDmaNWO = TLQ_DMA_NWO, kDmaNWT = TLQ_DMA_NWT;
 
 void gemm_tile_counts(int64_t n_tok, int64_t c_out, int64_t* tiles_o, int64_t* tiles_t) {
   *tiles_o = ceil_div(c_out, kBO);
@@ -592,8 +657,11 @@ static hipError_t launch_gemm(const GemmArgs& g, const char* name, hipStream_t s
   // the pipelined kernel needs whole k-tiles and 32-bit byte offsets inside a 256-row panel
   const bool dma = (g.c_in % kDmaBK) == 0 && g.ldw < (1 << 21) && g.ldx < (1 << 21);
   if (dma) {
-    if (!g.bf16) gemm_dma_kernel<F16, kDmaBK, kDmaStages, EPI><<<(unsigned)blocks, NT, 0, stream>>>(d);
-    else gemm_dma_kernel<BF16, kDmaBK, kDmaStages, EPI><<<(unsigned)blocks, NT, 0, stream>>>(d);
+    constexpr int NTD = kDmaNWO * kDmaNWT * 64;
+    if (!g.bf16)
+      gemm_dma_kernel<F16, kDmaBK, kDmaStages, kDmaNWO, kDmaNWT, EPI><<<(unsigned)blocks, NTD, 0, stream>>>(d);
+    else
+      gemm_dma_kernel<BF16, kDmaBK, kDmaStages, kDmaNWO, kDmaNWT, EPI><<<(unsigned)blocks, NTD, 0, stream>>>(d);
   } else {
     if (!g.bf16) gemm_kernel<F16, kBO, kBT, kWO, kWT, EPI><<<(unsigned)blocks, NT, 0, stream>>>(d);
     else gemm_kernel<BF16, kBO, kBT, kWO, kWT, EPI><<<(unsigned)blocks, NT, 0, stream>>>(d);
