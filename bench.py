@@ -23,37 +23,49 @@ if ROOT not in sys.path:
 
 METRIC = "candidate-scale evals/sec per layer + fused-kernel TFLOP/s (% fp16 MFMA peak)"
 PEAK_FP16_TFLOPS = 2500.0      # MI355X dense fp16 MFMA peak (published)
-# HBM bytes per gemm_loss launch measured with rocprofv3 --pmc (FETCH_SIZE + WRITE_SIZE,
-# scaled by a copy kernel of known size); None until a counter run has been committed
-# under profiles/.
-MEASURED_TRAFFIC_BYTES_PER_LAUNCH = None
+# Bytes per gemm_loss launch that cross the L2/fabric boundary, from two rocprofv3 --pmc
+# runs of this file (FETCH_SIZE, WRITE_SIZE), each scaled by what the same counter reads
+# for the known-size calibration copy below (x1.999 and x1.000); summary under profiles/.
+MEASURED_TRAFFIC_BYTES_PER_LAUNCH = 2.037e10
 
 
 def cpu_baseline(wl, orc, workload):
     """Time the oracle, as it stands, on a bounded sample of the same workload:
-    the q_proj-shaped linear, the first 4 calibration samples (2560 of 10240
-    tokens), 4 of the 20 candidates.  Reported as full-size evaluations per
-    second (the oracle's cost is linear in the token count)."""
+    the q_proj-shaped linear with all of its 10240 tokens and the whole
+    20-point grid (one of the step's seven searches).  Reported as candidate
+    evaluations per second."""
     import numpy as np
     try:
         from threadpoolctl import threadpool_info
         cores = max([i.get("num_threads", 1) for i in threadpool_info()] or [os.cpu_count() or 1])
     except Exception:
         cores = os.cpu_count() or 1
-    n_samp, cand = 4, [0, 5, 10, 15]
-    X = wl.make_tokens(workload, 0, samples=range(n_samp))
+    cand = list(range(workload.n_alpha))
+    X = wl.make_tokens(workload, 0)
     W = wl.make_weight(workload, 0)
-    w = wl.make_token_weights(workload, 0)[: X.shape[0]]
+    w = wl.make_token_weights(workload, 0)
     al = wl.alpha_grid(workload.n_alpha)[cand]
     Y = orc.ref_output(X, W).astype(np.float16)
     t0 = time.perf_counter()
     orc.scale_search(X, W, Y, w, workload.bits, workload.group, al)
     dt = time.perf_counter() - t0
-    frac = X.shape[0] / workload.n_tok
-    return {"value": len(cand) / dt * frac, "unit": "evals/s", "cores": int(cores), "kind": "oracle",
-            "sample": f"{workload.name} q_proj 4096x4096, {X.shape[0]} of {workload.n_tok} tokens, "
-                      f"{len(cand)} of {workload.n_alpha} candidates, {dt:.1f} s of numpy fp64; "
-                      "scaled linearly in tokens to full-size evaluations"}
+    return {"value": len(cand) / dt, "unit": "evals/s", "cores": int(cores), "kind": "oracle",
+            "sample": f"{workload.name} q_proj 4096x4096, all {X.shape[0]} tokens, "
+                      f"{len(cand)} of {workload.n_alpha} candidates, {dt:.1f} s of numpy fp64"}
+
+
+def mfma_ceiling():
+    """Context for the roofline fraction: what a register-only fp16 MFMA loop
+    sustains on this device with constant and with pseudo-random operands."""
+    import subprocess
+    exe = os.path.join(ROOT, "paper_2602_07899_amd", "mfma_ceiling")
+    if not os.path.exists(exe):
+        return None
+    try:
+        r = subprocess.run([exe], capture_output=True, text=True, timeout=60)
+        return json.loads(r.stdout.strip().splitlines()[-1]) if r.returncode == 0 else None
+    except Exception:
+        return None
 
 
 def main():
@@ -62,6 +74,8 @@ def main():
     ap.add_argument("--steps", type=int, default=5)
     ap.add_argument("--warmup", type=int, default=2)
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-ceiling", action="store_true",
+                    help="skip the register-only MFMA ceiling measurement (context only)")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on exactly one GPU (no sharding, no collectives); "
@@ -98,6 +112,10 @@ def main():
         ws_bytes = max(ws_bytes, tlq.scale_search_workspace_bytes(workload.n_tok, spec.c_in, spec.c_out,
                                                                   workload.n_alpha, p))
     workspace = torch.empty(ws_bytes, dtype=torch.uint8, device=dev)
+    # one device-to-device copy of known size (reads and writes 83,886,080 bytes): the
+    # calibration kernel for the FETCH_SIZE / WRITE_SIZE counters in profiling runs
+    calib = torch.empty_like(layers[0][1])
+    calib.copy_(layers[0][1])
     torch.cuda.synchronize()
 
     def step():
@@ -142,6 +160,8 @@ def main():
                     for k in kernels.values()},
         "best_alpha_index": best_idx,
     }
+    if not args.no_ceiling:
+        result["mfma_ceiling"] = mfma_ceiling()
     if not args.no_cpu_baseline:
         from oracle import tlq_oracle as orc
         result["cpu_baseline"] = cpu_baseline(wl, orc, workload)

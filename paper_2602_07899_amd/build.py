@@ -19,6 +19,7 @@ ROOT = os.path.dirname(HERE)
 CSRC = os.path.join(HERE, "csrc")
 OBJ = os.path.join(HERE, "_build")
 LIB = os.path.join(HERE, "libtlq.so")
+CEILING = os.path.join(HERE, "mfma_ceiling")
 
 SOURCES = ["api.hip", "stats.hip", "quant.hip", "gemm.hip", "profile.hip"]
 COMMON = ["--offload-arch=gfx950", "-O3", "-fPIC", "-std=c++17", "-I", os.path.join(ROOT, "include"),
@@ -62,6 +63,11 @@ def build(verbose: bool = True, extra=()) -> str:
         raise RuntimeError("link failed:\n" + r.stdout + r.stderr)
     import ctypes
     ctypes.CDLL(LIB)  # an unresolved symbol must fail the build, not the first caller
+    # stand-alone measurement of the sustained MFMA ceiling (used by bench.py for context)
+    r = subprocess.run([hipcc(), "--offload-arch=gfx950", "-O3", "-std=c++17", *COMMON[-4:],
+                        os.path.join(CSRC, "mfma_ceiling.hip"), "-o", CEILING], capture_output=True, text=True)
+    if r.returncode != 0:
+        raise RuntimeError("mfma_ceiling build failed:\n" + r.stdout + r.stderr)
     if verbose:
         print("built", LIB)
     return LIB
