@@ -99,6 +99,98 @@ __device__ __forceinline__ void store_y1(void* Y, int odt, int64_t idx, float y)
   else ((uint16_t*)Y)[idx] = odt == TLQ_F16 ? F16::from_float(y) : BF16::from_float(y);
 }
 
+
+// ---------------------------------------------------------------------------
+// Tile epilogue shared by both kernels.  Accumulator layout of a 32x32
+// fragment: lane holds column (lane%32) and rows 8*(v/4) + 4*(lane/32) + v%4,
+// v = 0..15.  The block's waves form an NWO x NWT grid; wave (wo, wt) owns
+// output rows [wo*WO, +WO) and tokens [wt*WT, +WT) of the tile at (o0, t0).
+// `red` holds one float per wave, `rows` NWO x BT floats (per-token row sums;
+// only used by EPI_LOSS_TOK).  Every wave of the block must call this.
+template <int EPI, int FA, int FB, int NWO, int NWT, int BT>
+__device__ __forceinline__ void tile_epilogue(const GemmDev& a, f32x16 (&acc)[FA][FB], int cand, int to,
+                                              int tt, int64_t o0, int64_t t0, int wo, int wt,
+                                              float* red, float* rows) {
+  constexpr int WO = FA * 32, WT = FB * 32, NW = NWO * NWT, NT = NW * 64;
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int frow = lane & 31, fhi = lane >> 5;
+  if (EPI == EPI_STORE) {
+#pragma unroll
+    for (int j = 0; j < FB; ++j) {
+      const int64_t t = t0 + wt * WT + j * 32 + frow;
+      if (t >= a.n_tok) continue;
+#pragma unroll
+      for (int i = 0; i < FA; ++i)
+#pragma unroll
+        for (int q = 0; q < 4; ++q) {
+          const int64_t o = o0 + wo * WO + i * 32 + q * 8 + fhi * 4;
+          float y[4] = {acc[i][j][q * 4], acc[i][j][q * 4 + 1], acc[i][j][q * 4 + 2], acc[i][j][q * 4 + 3]};
+          if (o + 3 < a.c_out) store_y4(a.Yout, a.odt, t * a.ldo + o, y);
+          else
+            for (int r = 0; r < 4; ++r)
+              if (o + r < a.c_out) store_y1(a.Yout, a.odt, t * a.ldo + o + r, y[r]);
+        }
+    }
+    return;
+  }
+  float part = 0.0f;
+#pragma unroll
+  for (int j = 0; j < FB; ++j) {
+    const int64_t t = t0 + wt * WT + j * 32 + frow;
+    const bool tok = t < a.n_tok;
+    float sumsq = 0.0f;
+    if (tok) {
+#pragma unroll
+      for (int i = 0; i < FA; ++i)
+#pragma unroll
+        for (int q = 0; q < 4; ++q) {
+          const int64_t o = o0 + wo * WO + i * 32 + q * 8 + fhi * 4;
+          if (o + 3 < a.c_out) {
+            float y[4];
+            load_y4(a.Yref, a.ydt, t * a.ldy + o, y);
+#pragma unroll
+            for (int r = 0; r < 4; ++r) {
+              const float d = y[r] - acc[i][j][q * 4 + r];
+              sumsq += d * d;
+            }
+          } else {
+            for (int r = 0; r < 4; ++r)
+              if (o + r < a.c_out) {
+                const float d = load_y(a.Yref, a.ydt, t * a.ldy + o + r) - acc[i][j][q * 4 + r];
+                sumsq += d * d;
+              }
+          }
+        }
+      part += a.token_w[t] * sumsq;
+    }
+    if (EPI == EPI_LOSS_TOK) {
+      const float both = sumsq + __shfl_xor(sumsq, 32, 64);
+      if (fhi == 0) rows[wo * BT + wt * WT + j * 32 + frow] = both;
+    }
+  }
+#pragma unroll
+  for (int off = 32; off >= 1; off >>= 1) part += __shfl_xor(part, off, 64);
+  if (lane == 0) red[wave] = part;
+  __syncthreads();
+  if (tid == 0) {
+    float s = 0.0f;
+#pragma unroll
+    for (int w = 0; w < NW; ++w) s += red[w];
+    a.partial[((int64_t)cand * a.tiles_o + to) * a.tiles_t + tt] = s;
+  }
+  if (EPI == EPI_LOSS_TOK) {
+    for (int i = tid; i < BT; i += NT) {
+      const int64_t t = t0 + i;
+      if (t < a.n_tok) {
+        float s = 0.0f;
+#pragma unroll
+        for (int w = 0; w < NWO; ++w) s += rows[w * BT + i];
+        a.tok_partial[(int64_t)to * a.n_tok + t] = s;
+      }
+    }
+  }
+}
+
 template <typename T, int BO, int BT, int WO, int WT, int EPI>
 __global__ __launch_bounds__((BO / WO) * (BT / WT) * 64) void gemm_kernel(GemmDev a) {
   constexpr int NWO = BO / WO, NWT = BT / WT, NW = NWO * NWT, NT = NW * 64;
@@ -211,87 +303,10 @@ __global__ __launch_bounds__((BO / WO) * (BT / WT) * 64) void gemm_kernel(GemmDe
     __syncthreads();
   }
 
-  // ---- epilogue.  Accumulator layout of a 32x32 fragment: lane holds column
-  // (lane%32) and rows 8*(v/4) + 4*(lane/32) + v%4 for v = 0..15.
-  if (EPI == EPI_STORE) {
-#pragma unroll
-    for (int j = 0; j < FB; ++j) {
-      const int64_t t = t0 + wt * WT + j * 32 + frow;
-      if (t >= a.n_tok) continue;
-#pragma unroll
-      for (int i = 0; i < FA; ++i)
-#pragma unroll
-        for (int q = 0; q < 4; ++q) {
-          const int64_t o = o0 + wo * WO + i * 32 + q * 8 + fhi * 4;
-          float y[4] = {acc[i][j][q * 4], acc[i][j][q * 4 + 1], acc[i][j][q * 4 + 2], acc[i][j][q * 4 + 3]};
-          if (o + 3 < a.c_out) store_y4(a.Yout, a.odt, t * a.ldo + o, y);
-          else
-            for (int r = 0; r < 4; ++r)
-              if (o + r < a.c_out) store_y1(a.Yout, a.odt, t * a.ldo + o + r, y[r]);
-        }
-    }
-    return;
-  }
-
-  float part = 0.0f;
-  float* rows = reinterpret_cast<float*>(lds);  // [NWO][BT] row sums, reuses the tile memory
-#pragma unroll
-  for (int j = 0; j < FB; ++j) {
-    const int64_t t = t0 + wt * WT + j * 32 + frow;
-    const bool tok = t < a.n_tok;
-    float sumsq = 0.0f;
-    if (tok) {
-#pragma unroll
-      for (int i = 0; i < FA; ++i)
-#pragma unroll
-        for (int q = 0; q < 4; ++q) {
-          const int64_t o = o0 + wo * WO + i * 32 + q * 8 + fhi * 4;
-          if (o + 3 < a.c_out) {
-            float y[4];
-            load_y4(a.Yref, a.ydt, t * a.ldy + o, y);
-#pragma unroll
-            for (int r = 0; r < 4; ++r) {
-              const float d = y[r] - acc[i][j][q * 4 + r];
-              sumsq += d * d;
-            }
-          } else {
-            for (int r = 0; r < 4; ++r)
-              if (o + r < a.c_out) {
-                const float d = load_y(a.Yref, a.ydt, t * a.ldy + o + r) - acc[i][j][q * 4 + r];
-                sumsq += d * d;
-              }
-          }
-        }
-      part += a.token_w[t] * sumsq;
-    }
-    if (EPI == EPI_LOSS_TOK) {
-      const float both = sumsq + __shfl_xor(sumsq, 32, 64);
-      if (fhi == 0) rows[wo * BT + wt * WT + j * 32 + frow] = both;
-    }
-  }
-#pragma unroll
-  for (int off = 32; off >= 1; off >>= 1) part += __shfl_xor(part, off, 64);
-  if (lane == 0) red[wave] = part;
-  __syncthreads();
-  if (tid == 0) {
-    float s = 0.0f;
-#pragma unroll
-    for (int w = 0; w < NW; ++w) s += red[w];
-    a.partial[((int64_t)cand * a.tiles_o + to) * a.tiles_t + tt] = s;
-  }
-  if (EPI == EPI_LOSS_TOK) {
-    for (int i = tid; i < BT; i += NT) {
-      const int64_t t = t0 + i;
-      if (t < a.n_tok) {
-        float s = 0.0f;
-#pragma unroll
-        for (int w = 0; w < NWO; ++w) s += rows[w * BT + i];
-        a.tok_partial[(int64_t)to * a.n_tok + t] = s;
-      }
-    }
-  }
+  // the tile memory is free now: row sums of the per-token variant reuse it
+  tile_epilogue<EPI, FA, FB, NWO, NWT, BT>(a, acc, cand, to, tt, o0, t0, wo, wt, red,
+                                           reinterpret_cast<float*>(lds));
 }
-
 
 // ---------------------------------------------------------------------------
 // Pipelined variant for c_in % BK == 0 (every group-128 workload).
@@ -356,7 +371,7 @@ __device__ __forceinline__ void wait_vmcnt() {
 template <typename T, int BK_, int NSTAGE, int NWO, int NWT, int EPI>
 __global__ __launch_bounds__(NWO * NWT * 64) void gemm_dma_kernel(GemmDev a) {
 #if defined(__HIP_DEVICE_COMPILE__)  // the body uses gfx950 builtins the host pass cannot parse
-  constexpr int BO = 256, BT = 256, WO = BO / NWO, WT = BT / NWT, NW = NWO * NWT, NT = NW * 64;
+  constexpr int BO = 256, BT = 256, WO = BO / NWO, WT = BT / NWT, NW = NWO * NWT;
   constexpr int FA = WO / 32, FB = WT / 32, NF = FA + FB, KK = BK_ / 16;
   static_assert(NF == 6 || NF == 8, "fragment count");
   constexpr int RB = BK_ * 2;             // bytes per LDS row
@@ -532,83 +547,10 @@ __global__ __launch_bounds__(NWO * NWT * 64) void gemm_dma_kernel(GemmDev a) {
   wait_vmcnt<0>();
   __syncthreads();
 
-  // ---- epilogue (same as gemm_kernel)
-  if (EPI == EPI_STORE) {
-#pragma unroll
-    for (int j = 0; j < FB; ++j) {
-      const int64_t t = t0 + wt * WT + j * 32 + frow;
-      if (t >= a.n_tok) continue;
-#pragma unroll
-      for (int i = 0; i < FA; ++i)
-#pragma unroll
-        for (int q = 0; q < 4; ++q) {
-          const int64_t o = o0 + wo * WO + i * 32 + q * 8 + fhi * 4;
-          float y[4] = {acc[i][j][q * 4], acc[i][j][q * 4 + 1], acc[i][j][q * 4 + 2], acc[i][j][q * 4 + 3]};
-          if (o + 3 < a.c_out) store_y4(a.Yout, a.odt, t * a.ldo + o, y);
-          else
-            for (int r = 0; r < 4; ++r)
-              if (o + r < a.c_out) store_y1(a.Yout, a.odt, t * a.ldo + o + r, y[r]);
-        }
-    }
-    return;
-  }
-  float part = 0.0f;
-  float* rows = reinterpret_cast<float*>(lds);
-#pragma unroll
-  for (int j = 0; j < FB; ++j) {
-    const int64_t t = t0 + wt * WT + j * 32 + frow;
-    const bool tok = t < a.n_tok;
-    float sumsq = 0.0f;
-    if (tok) {
-#pragma unroll
-      for (int i = 0; i < FA; ++i)
-#pragma unroll
-        for (int q = 0; q < 4; ++q) {
-          const int64_t o = o0 + wo * WO + i * 32 + q * 8 + fhi * 4;
-          if (o + 3 < a.c_out) {
-            float y[4];
-            load_y4(a.Yref, a.ydt, t * a.ldy + o, y);
-#pragma unroll
-            for (int r = 0; r < 4; ++r) {
-              const float d = y[r] - acc[i][j][q * 4 + r];
-              sumsq += d * d;
-            }
-          } else {
-            for (int r = 0; r < 4; ++r)
-              if (o + r < a.c_out) {
-                const float d = load_y(a.Yref, a.ydt, t * a.ldy + o + r) - acc[i][j][q * 4 + r];
-                sumsq += d * d;
-              }
-          }
-        }
-      part += a.token_w[t] * sumsq;
-    }
-    if (EPI == EPI_LOSS_TOK) {
-      const float both = sumsq + __shfl_xor(sumsq, 32, 64);
-      if (fhi == 0) rows[wo * BT + wt * WT + j * 32 + frow] = both;
-    }
-  }
-#pragma unroll
-  for (int off = 32; off >= 1; off >>= 1) part += __shfl_xor(part, off, 64);
-  if (lane == 0) red[wave] = part;
-  __syncthreads();
-  if (tid == 0) {
-    float s = 0.0f;
-#pragma unroll
-    for (int w = 0; w < NW; ++w) s += red[w];
-    a.partial[((int64_t)cand * a.tiles_o + to) * a.tiles_t + tt] = s;
-  }
-  if (EPI == EPI_LOSS_TOK) {
-    for (int i = tid; i < BT; i += NT) {
-      const int64_t t = t0 + i;
-      if (t < a.n_tok) {
-        float s = 0.0f;
-#pragma unroll
-        for (int w = 0; w < NWO; ++w) s += rows[w * BT + i];
-        a.tok_partial[(int64_t)to * a.n_tok + t] = s;
-      }
-    }
-  }
+  // every LDS-DMA write has landed and every wave is past its last fragment read:
+  // the tile memory is free for the per-token row sums
+  tile_epilogue<EPI, FA, FB, NWO, NWT, BT>(a, acc, cand, to, tt, o0, t0, wo, wt, red,
+                                           reinterpret_cast<float*>(lds));
 #endif
 }
 
