@@ -33,6 +33,10 @@
  *     and of `group` (TLQ_ERR_SHAPE otherwise).
  *   - Calls on different streams may run concurrently if their workspaces and
  *     outputs are disjoint.
+ *   - x_dtype = BF16: inputs and 16-bit outputs are bf16.  Operands the library
+ *     computes itself (the folded weights deq/s) are kept in fp16, and the tokens
+ *     are re-expressed in fp16 in the workspace (exact for bf16 values after a
+ *     power-of-two prescale), so bf16 inputs get the same loss accuracy as fp16.
  */
 #ifndef TLQ_H
 #define TLQ_H
@@ -150,7 +154,8 @@ tlq_status tlq_ref_output(const void* X, int64_t n_tok, int64_t c_in, int64_t ld
 /* ---- S6: quantisation-exposed propagation (Sec. 3.2.1 PassAct2):
  * X_next = f_q(X; s) = (X diag(s)^-1) Q_w(W diag(s))^T stored as x_dtype.
  * s: in float [c_in] (e.g. best_scales); X_next: out [n_tok, c_out]. */
-size_t tlq_apply_best_workspace_bytes(int64_t c_in, int64_t c_out, const tlq_params* p);
+size_t tlq_apply_best_workspace_bytes(int64_t n_tok, int64_t c_in, int64_t c_out,
+                                      const tlq_params* p);
 tlq_status tlq_apply_best(const void* X, int64_t n_tok, int64_t c_in, int64_t ldx,
                           const void* W, int64_t c_out, int64_t ldw, const float* s,
                           const tlq_params* p, void* X_next, int64_t ld_next,

@@ -55,17 +55,14 @@ tlq_status hip_status(hipError_t e) { return e == hipSuccess ? TLQ_OK : TLQ_ERR_
 #define TLQ_TRY(expr) do { tlq_status st_ = (expr); if (st_ != TLQ_OK) return st_; } while (0)
 #define TLQ_HIP(expr) do { if ((expr) != hipSuccess) return TLQ_ERR_LAUNCH; } while (0)
 
-__global__ void recip_kernel(const float* __restrict__ s, int64_t n, float* __restrict__ inv) {
-  const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
-  if (i < n) inv[i] = (float)(1.0 / (double)s[i]);
-}
-
 // ---- workspace plans -----------------------------------------------------------
+// With bf16 inputs the computed operand is kept in fp16 and the tokens are re-expressed
+// exactly in fp16 (see launch_xprep): `xh` holds them, `xmax` the bits of max|X|.
 struct SearchPlan {
   double* xs_partial; float* x_stat; float* s_table; float* inv_table; float* partial;
-  uint16_t* what; size_t bytes; int64_t tiles_o, tiles_t;
+  uint16_t* what; uint32_t* xmax; uint16_t* xh; size_t bytes; int64_t tiles_o, tiles_t;
 };
-SearchPlan plan_search(void* ws, int64_t n_tok, int64_t c_in, int64_t c_out, int n_alpha) {
+SearchPlan plan_search(void* ws, int64_t n_tok, int64_t c_in, int64_t c_out, int n_alpha, bool bf16) {
   SearchPlan s;
   Carver c(ws);
   gemm_tile_counts(n_tok, c_out, &s.tiles_o, &s.tiles_t);
@@ -75,20 +72,25 @@ SearchPlan plan_search(void* ws, int64_t n_tok, int64_t c_in, int64_t c_out, int
   s.inv_table = c.take<float>((size_t)n_alpha * c_in);
   s.partial = c.take<float>((size_t)n_alpha * s.tiles_o * s.tiles_t);
   s.what = c.take<uint16_t>((size_t)n_alpha * c_out * c_in);
+  s.xmax = c.take<uint32_t>(1);
+  s.xh = bf16 ? c.take<uint16_t>((size_t)n_tok * c_in) : nullptr;
   s.bytes = c.off;
   return s;
 }
 
 struct ErrPlan {
-  float* partial; float* tok_partial; uint16_t* folded; size_t bytes; int64_t tiles_o, tiles_t;
+  float* partial; float* tok_partial; uint16_t* folded; uint32_t* xmax; uint16_t* xh; size_t bytes;
+  int64_t tiles_o, tiles_t;
 };
-ErrPlan plan_err(void* ws, int64_t n_tok, int64_t c_in, int64_t c_out) {
+ErrPlan plan_err(void* ws, int64_t n_tok, int64_t c_in, int64_t c_out, bool bf16) {
   ErrPlan e;
   Carver c(ws);
   gemm_tile_counts(n_tok, c_out, &e.tiles_o, &e.tiles_t);
   e.partial = c.take<float>((size_t)e.tiles_o * e.tiles_t);
   e.tok_partial = c.take<float>((size_t)e.tiles_o * n_tok);
   e.folded = c.take<uint16_t>((size_t)c_out * c_in);
+  e.xmax = c.take<uint32_t>(1);
+  e.xh = bf16 ? c.take<uint16_t>((size_t)n_tok * c_in) : nullptr;
   e.bytes = c.off;
   return e;
 }
@@ -135,7 +137,7 @@ tlq_status tlq_scale_table(const float* x_stat, int64_t c_in, const float* alpha
                            int32_t n_alpha, float* s_table, void* stream) {
   if (!x_stat || !alpha_grid || !s_table) return TLQ_ERR_NULL;
   if (c_in <= 0 || n_alpha <= 0 || n_alpha > TLQ_MAX_ALPHA) return TLQ_ERR_SHAPE;
-  return hip_status(launch_scale_table(x_stat, c_in, alpha_grid, n_alpha, s_table, nullptr,
+  return hip_status(launch_scale_table(x_stat, c_in, alpha_grid, n_alpha, s_table, nullptr, nullptr,
                                        (hipStream_t)stream));
 }
 
@@ -165,7 +167,7 @@ tlq_status tlq_fake_quant(const void* W, int64_t c_out, int64_t c_in, int64_t ld
 size_t tlq_weighted_layer_err_workspace_bytes(int64_t n_tok, int64_t c_in, int64_t c_out,
                                               const tlq_params* p) {
   if (n_tok <= 0 || c_in <= 0 || c_out <= 0 || check_params(p) != TLQ_OK) return 0;
-  return plan_err(nullptr, n_tok, c_in, c_out).bytes;
+  return plan_err(nullptr, n_tok, c_in, c_out, p->x_dtype == TLQ_BF16).bytes;
 }
 
 tlq_status tlq_weighted_layer_err(const void* X, int64_t n_tok, int64_t c_in, int64_t ldx,
@@ -185,12 +187,18 @@ tlq_status tlq_weighted_layer_err(const void* X, int64_t n_tok, int64_t c_in, in
                    tlq_weighted_layer_err_workspace_bytes(n_tok, c_in, c_out, p)));
   hipStream_t st = (hipStream_t)stream;
   const bool bf16 = p->x_dtype == TLQ_BF16;
-  ErrPlan e = plan_err(workspace, n_tok, c_in, c_out);
+  ErrPlan e = plan_err(workspace, n_tok, c_in, c_out, bf16);
   GemmArgs g{};
   g.X = X; g.n_tok = n_tok; g.c_in = c_in; g.ldx = ldx;
   g.Wh = Wdq; g.c_out = c_out; g.ldw = ldw; g.w_cand_stride = 0; g.n_cand = 1; g.bf16 = bf16;
   if (inv_s) {
-    TLQ_HIP(launch_fold_scale(Wdq, c_out, c_in, ldw, bf16, inv_s, e.folded, st));
+    // the folded operand is a computed value: with bf16 inputs keep it (and X) in fp16
+    if (bf16) {
+      TLQ_HIP(launch_xprep(X, n_tok, c_in, ldx, e.xmax, e.xh, st));
+      g.X = e.xh; g.ldx = c_in; g.bf16 = false;
+    }
+    TLQ_HIP(launch_fold_scale(Wdq, c_out, c_in, ldw, bf16, inv_s, bf16 ? e.xmax : nullptr, bf16,
+                              e.folded, st));
     g.Wh = e.folded; g.ldw = c_in;
   }
   g.Yref = Y_ref; g.ldy = ldy; g.yref_dtype = p->yref_dtype; g.token_w = token_w;
@@ -209,7 +217,7 @@ size_t tlq_scale_search_workspace_bytes(int64_t n_tok, int64_t c_in, int64_t c_o
   if (n_tok <= 0 || c_in <= 0 || c_out <= 0 || n_alpha <= 0 || n_alpha > TLQ_MAX_ALPHA ||
       check_params(p) != TLQ_OK)
     return 0;
-  return plan_search(nullptr, n_tok, c_in, c_out, n_alpha).bytes;
+  return plan_search(nullptr, n_tok, c_in, c_out, n_alpha, p->x_dtype == TLQ_BF16).bytes;
 }
 
 tlq_status tlq_scale_search(const void* X, int64_t n_tok, int64_t c_in, int64_t ldx,
@@ -232,15 +240,17 @@ tlq_status tlq_scale_search(const void* X, int64_t n_tok, int64_t c_in, int64_t 
                    tlq_scale_search_workspace_bytes(n_tok, c_in, c_out, n_alpha, p)));
   hipStream_t st = (hipStream_t)stream;
   const bool bf16 = p->x_dtype == TLQ_BF16;
-  SearchPlan s = plan_search(workspace, n_tok, c_in, c_out, n_alpha);
+  SearchPlan s = plan_search(workspace, n_tok, c_in, c_out, n_alpha, bf16);
 
   const float* x_stat = x_stat_in;
   if (!x_stat) {  // S0
     TLQ_HIP(launch_xstat(X, n_tok, c_in, ldx, bf16, p->xstat_kind, s.xs_partial, s.x_stat, st));
     x_stat = s.x_stat;
   }
+  if (bf16) TLQ_HIP(launch_xprep(X, n_tok, c_in, ldx, s.xmax, s.xh, st));
   // S1
-  TLQ_HIP(launch_scale_table(x_stat, c_in, alpha_grid, n_alpha, s.s_table, s.inv_table, st));
+  TLQ_HIP(launch_scale_table(x_stat, c_in, alpha_grid, n_alpha, s.s_table, s.inv_table,
+                             bf16 ? s.xmax : nullptr, st));
   if (s_table_out)
     TLQ_HIP(hipMemcpyAsync(s_table_out, s.s_table, (size_t)n_alpha * c_in * sizeof(float),
                            hipMemcpyDeviceToDevice, st));
@@ -249,13 +259,13 @@ tlq_status tlq_scale_search(const void* X, int64_t n_tok, int64_t c_in, int64_t 
   q.W = W; q.c_out = c_out; q.c_in = c_in; q.ldw = ldw; q.bf16 = bf16;
   q.bits = p->bits; q.group = p->group; q.symmetric = p->symmetric;
   q.s_table = s.s_table; q.inv_table = s.inv_table; q.n_cand = n_alpha;
-  q.what = s.what; q.what_cand_stride = c_out * c_in;
+  q.what = s.what; q.what_cand_stride = c_out * c_in; q.what_f16 = true;
   TLQ_HIP(launch_fake_quant(q, st));
-  // S3 + S4: one launch over the stacked candidates
+  // S3 + S4: one launch over the stacked candidates (fp16 operands in either case)
   GemmArgs g{};
-  g.X = X; g.n_tok = n_tok; g.c_in = c_in; g.ldx = ldx;
+  g.X = bf16 ? (const void*)s.xh : X; g.n_tok = n_tok; g.c_in = c_in; g.ldx = bf16 ? c_in : ldx;
   g.Wh = s.what; g.c_out = c_out; g.ldw = c_in; g.w_cand_stride = c_out * c_in;
-  g.n_cand = n_alpha; g.bf16 = bf16;
+  g.n_cand = n_alpha; g.bf16 = false;
   g.Yref = Y_ref; g.ldy = ldy; g.yref_dtype = p->yref_dtype; g.token_w = token_w;
   g.partial = s.partial; g.tok_partial = nullptr;
   TLQ_HIP(launch_gemm_loss(g, st));
@@ -285,9 +295,11 @@ tlq_status tlq_ref_output(const void* X, int64_t n_tok, int64_t c_in, int64_t ld
 }
 
 // ------------------------------------------------------------------------ S6
-size_t tlq_apply_best_workspace_bytes(int64_t c_in, int64_t c_out, const tlq_params* p) {
-  if (c_in <= 0 || c_out <= 0 || check_params(p) != TLQ_OK) return 0;
-  return align_up((size_t)c_in * sizeof(float), 256) + align_up((size_t)c_out * c_in * 2, 256);
+size_t tlq_apply_best_workspace_bytes(int64_t n_tok, int64_t c_in, int64_t c_out,
+                                      const tlq_params* p) {
+  if (n_tok <= 0 || c_in <= 0 || c_out <= 0 || check_params(p) != TLQ_OK) return 0;
+  return align_up((size_t)c_in * sizeof(float), 256) + align_up((size_t)c_out * c_in * 2, 256) + 256 +
+         (p->x_dtype == TLQ_BF16 ? align_up((size_t)n_tok * c_in * 2, 256) : 0);
 }
 
 tlq_status tlq_apply_best(const void* X, int64_t n_tok, int64_t c_in, int64_t ldx,
@@ -302,22 +314,25 @@ tlq_status tlq_apply_best(const void* X, int64_t n_tok, int64_t c_in, int64_t ld
   if (!mat16_aligned(X, ldx) || !mat16_aligned(W, ldw) || !mat16_aligned(X_next, ld_next) ||
       !aligned(s, 16))
     return TLQ_ERR_ALIGN;
-  TLQ_TRY(check_ws(workspace, workspace_bytes, tlq_apply_best_workspace_bytes(c_in, c_out, p)));
+  TLQ_TRY(check_ws(workspace, workspace_bytes, tlq_apply_best_workspace_bytes(n_tok, c_in, c_out, p)));
   hipStream_t st = (hipStream_t)stream;
   const bool bf16 = p->x_dtype == TLQ_BF16;
   Carver c(workspace);
   float* inv = c.take<float>((size_t)c_in);
   uint16_t* what = c.take<uint16_t>((size_t)c_out * c_in);
-  recip_kernel<<<(unsigned)ceil_div(c_in, 256), 256, 0, st>>>(s, c_in, inv);
-  TLQ_HIP(hipGetLastError());
+  uint32_t* xmax = c.take<uint32_t>(1);
+  uint16_t* xh = bf16 ? c.take<uint16_t>((size_t)n_tok * c_in) : nullptr;
+  if (bf16) TLQ_HIP(launch_xprep(X, n_tok, c_in, ldx, xmax, xh, st));
+  TLQ_HIP(launch_recip(s, c_in, bf16 ? xmax : nullptr, inv, st));
   QuantArgs q{};
   q.W = W; q.c_out = c_out; q.c_in = c_in; q.ldw = ldw; q.bf16 = bf16;
   q.bits = p->bits; q.group = p->group; q.symmetric = p->symmetric;
   q.s_table = s; q.inv_table = inv; q.n_cand = 1; q.what = what; q.what_cand_stride = 0;
+  q.what_f16 = true;
   TLQ_HIP(launch_fake_quant(q, st));
   GemmArgs g{};
-  g.X = X; g.n_tok = n_tok; g.c_in = c_in; g.ldx = ldx;
-  g.Wh = what; g.c_out = c_out; g.ldw = c_in; g.w_cand_stride = 0; g.n_cand = 1; g.bf16 = bf16;
+  g.X = bf16 ? (const void*)xh : X; g.n_tok = n_tok; g.c_in = c_in; g.ldx = bf16 ? c_in : ldx;
+  g.Wh = what; g.c_out = c_out; g.ldw = c_in; g.w_cand_stride = 0; g.n_cand = 1; g.bf16 = false;
   g.Yout = X_next; g.ldo = ld_next; g.yout_dtype = p->x_dtype;
   return hip_status(launch_gemm_store(g, st));
 }

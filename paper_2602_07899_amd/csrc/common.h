@@ -52,8 +52,27 @@ int xstat_chunks(int64_t n_tok);
 hipError_t launch_xstat(const void* X, int64_t n_tok, int64_t c_in, int64_t ldx, bool bf16,
                         int kind, double* partial, float* x_stat, hipStream_t stream);
 // S1
+// inv_table (optional) = 2^shift / s, where shift comes from `xmax_bits` (see launch_xprep) or is 0
 hipError_t launch_scale_table(const float* x_stat, int64_t c_in, const float* alpha, int n_alpha,
-                              float* s_table, float* inv_table, hipStream_t stream);
+                              float* s_table, float* inv_table, const uint32_t* xmax_bits,
+                              hipStream_t stream);
+// inv[c] = 2^shift / s[c]
+hipError_t launch_recip(const float* s, int64_t c_in, const uint32_t* xmax_bits, float* inv,
+                        hipStream_t stream);
+
+// bf16 activations re-expressed in fp16.  A bf16 value has 8 significant bits, so
+// X * 2^-shift is exact in fp16 once shift keeps the largest magnitude below 2^15
+// (values more than 2^32 below that maximum lose low bits - far below anything the
+// loss can see).  xmax_bits receives the bit pattern of max|X|; every consumer derives
+// the same shift from it.  The folded weights carry the factor 2^shift, so the
+// contraction is unchanged while its computed operand is rounded to 11 instead of 8
+// significant bits.
+hipError_t launch_xprep(const void* X, int64_t n_tok, int64_t c_in, int64_t ldx, uint32_t* xmax_bits,
+                        void* Xh, hipStream_t stream);
+__host__ __device__ inline int shift_from_bf16_bits(uint32_t bits) {
+  const int k = (int)((bits >> 7) & 0xffu) - 141;  // |x| < 2^(e-126); want < 2^15
+  return k < 0 ? 0 : (k > 24 ? 24 : k);
+}
 
 // S2.  Quantises W*diag(s_k) for n_cand candidates (s_table row stride c_in).
 // what:  folded operand deq/s as 16-bit [n_cand, c_out, c_in] (row stride c_in) or NULL
@@ -65,13 +84,15 @@ struct QuantArgs {
   const float* inv_table; // [n_cand, c_in] or NULL (ones); used only for `what`
   int n_cand;
   void* what; int64_t what_cand_stride;  // elements between candidates
+  bool what_f16;          // round `what` to fp16 even when W is bf16
   uint8_t* codes; uint8_t* zp; float* delta; void* wdq; int64_t ld_dq;
 };
 hipError_t launch_fake_quant(const QuantArgs& a, hipStream_t stream);
 
 // Wout[o,c] = round16(Win[o,c] * inv_s[c])
 hipError_t launch_fold_scale(const void* Win, int64_t c_out, int64_t c_in, int64_t ldw, bool bf16,
-                             const float* inv_s, void* Wout, hipStream_t stream);
+                             const float* inv_s, const uint32_t* xmax_bits, bool out_f16, void* Wout,
+                             hipStream_t stream);
 
 // S3+S4 / plain GEMM with store epilogue.
 struct GemmArgs {

@@ -19,7 +19,7 @@ struct QuantDev {
   float qmax, qlo, qhi; int half;  // asym: codes in [0,qmax]; sym: q in [qlo,qhi], half = 2^(bits-1)
   int group;                        // resolved group size (>= 8)
   const float* s_table; const float* inv_table; int n_cand;
-  uint16_t* what; int64_t what_cand_stride;
+  uint16_t* what; int64_t what_cand_stride; bool what_f16;
   uint8_t* codes; uint8_t* zp; float* delta; uint16_t* wdq; int64_t ld_dq;
 };
 
@@ -123,7 +123,8 @@ __global__ __launch_bounds__(256) void quant_pow2_kernel(QuantDev a) {
       float code, deq;
       quant_one<SYM>(ws[j], delta, zpf, a, code, deq);
       cw[j >> 2] |= ((uint32_t)code & 0xffu) << ((j & 3) * 8);
-      hw[j >> 1] |= (uint32_t)T::from_float(deq * inv[j]) << ((j & 1) * 16);
+      const float folded = deq * inv[j];
+      hw[j >> 1] |= (uint32_t)(a.what_f16 ? F16::from_float(folded) : T::from_float(folded)) << ((j & 1) * 16);
       dw[j >> 1] |= (uint32_t)T::from_float(deq) << ((j & 1) * 16);
     }
     if (!active) continue;
@@ -172,7 +173,11 @@ __global__ __launch_bounds__(256) void quant_any_kernel(QuantDev a) {
       float code, deq;
       quant_one<SYM>(ws, delta, zpf, a, code, deq);
       if (a.what)
-        a.what[(int64_t)k * a.what_cand_stride + row * a.c_in + c] = T::from_float(deq * (ik ? ik[c] : 1.0f));
+        {
+          const float folded = deq * (ik ? ik[c] : 1.0f);
+          a.what[(int64_t)k * a.what_cand_stride + row * a.c_in + c] =
+              a.what_f16 ? F16::from_float(folded) : T::from_float(folded);
+        }
       if (k == 0) {
         if (a.codes) a.codes[row * a.c_in + c] = (uint8_t)code;
         if (a.wdq) a.wdq[row * a.ld_dq + c] = T::from_float(deq);
@@ -193,7 +198,7 @@ hipError_t launch_fake_quant(const QuantArgs& q, hipStream_t stream) {
   d.qlo = -(float)d.half; d.qhi = (float)(d.half - 1);
   d.group = q.group == 0 ? (int)q.c_in : q.group;
   d.s_table = q.s_table; d.inv_table = q.inv_table; d.n_cand = q.n_cand;
-  d.what = (uint16_t*)q.what; d.what_cand_stride = q.what_cand_stride;
+  d.what = (uint16_t*)q.what; d.what_cand_stride = q.what_cand_stride; d.what_f16 = q.what_f16;
   d.codes = q.codes; d.zp = q.zp; d.delta = q.delta; d.wdq = (uint16_t*)q.wdq; d.ld_dq = q.ld_dq;
   const bool pow2 = d.group >= 8 && d.group <= 512 && (d.group & (d.group - 1)) == 0;
   const double bytes = (double)q.c_out * (double)q.c_in * (2.0 + 2.0 * (q.what ? q.n_cand : 0) +
@@ -219,10 +224,11 @@ hipError_t launch_fake_quant(const QuantArgs& q, hipStream_t stream) {
 }
 
 // Wout[o,c] = round16(Win[o,c] * inv_s[c]); dense output, row stride c_in.
-template <typename T>
+template <typename T, typename TO>
 __global__ __launch_bounds__(256) void fold_scale_kernel(const uint16_t* __restrict__ Win,
                                                          int64_t c_out, int64_t c_in, int64_t ldw,
                                                          const float* __restrict__ inv_s,
+                                                         const uint32_t* __restrict__ xmax_bits,
                                                          uint16_t* __restrict__ Wout) {
   const int64_t chunks = c_in / 8;
   const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
@@ -231,20 +237,26 @@ __global__ __launch_bounds__(256) void fold_scale_kernel(const uint16_t* __restr
   const uint4 v = *reinterpret_cast<const uint4*>(Win + row * ldw + c);
   const uint32_t u[4] = {v.x, v.y, v.z, v.w};
   uint32_t o[4] = {0, 0, 0, 0};
+  const float up = xmax_bits
+      ? __builtin_bit_cast(float, (uint32_t)(127 + shift_from_bf16_bits(*xmax_bits)) << 23) : 1.0f;
 #pragma unroll
   for (int j = 0; j < 8; ++j) {
     const float f = T::to_float((uint16_t)(u[j >> 1] >> ((j & 1) * 16))) * (inv_s ? inv_s[c + j] : 1.0f);
-    o[j >> 1] |= (uint32_t)T::from_float(f) << ((j & 1) * 16);
+    o[j >> 1] |= (uint32_t)TO::from_float(f * up) << ((j & 1) * 16);
   }
   *reinterpret_cast<uint4*>(Wout + row * c_in + c) = make_uint4(o[0], o[1], o[2], o[3]);
 }
 
 hipError_t launch_fold_scale(const void* Win, int64_t c_out, int64_t c_in, int64_t ldw, bool bf16,
-                             const float* inv_s, void* Wout, hipStream_t stream) {
+                             const float* inv_s, const uint32_t* xmax_bits, bool out_f16, void* Wout,
+                             hipStream_t stream) {
   ProfScope ps("fold_scale", stream, 4.0 * (double)c_out * (double)c_in);
   const unsigned grid = (unsigned)ceil_div(c_out * (c_in / 8), 256);
-  if (!bf16) fold_scale_kernel<F16><<<grid, 256, 0, stream>>>((const uint16_t*)Win, c_out, c_in, ldw, inv_s, (uint16_t*)Wout);
-  else fold_scale_kernel<BF16><<<grid, 256, 0, stream>>>((const uint16_t*)Win, c_out, c_in, ldw, inv_s, (uint16_t*)Wout);
+  const uint16_t* in = (const uint16_t*)Win;
+  uint16_t* out = (uint16_t*)Wout;
+  if (!bf16) fold_scale_kernel<F16, F16><<<grid, 256, 0, stream>>>(in, c_out, c_in, ldw, inv_s, xmax_bits, out);
+  else if (out_f16) fold_scale_kernel<BF16, F16><<<grid, 256, 0, stream>>>(in, c_out, c_in, ldw, inv_s, xmax_bits, out);
+  else fold_scale_kernel<BF16, BF16><<<grid, 256, 0, stream>>>(in, c_out, c_in, ldw, inv_s, xmax_bits, out);
   return hipGetLastError();
 }
 

@@ -99,9 +99,15 @@ hipError_t launch_xstat(const void* X, int64_t n_tok, int64_t c_in, int64_t ldx,
 // ------------------------------------------------------------ S1 scale table
 // Sec. 3.1.2 scale equation: s = x_stat^alpha, evaluated in double and rounded
 // once; the reciprocal table feeds the folded GEMM operand deq / s.
+__device__ __forceinline__ double pow2_shift(const uint32_t* xmax_bits) {
+  const int k = xmax_bits ? shift_from_bf16_bits(*xmax_bits) : 0;
+  return (double)__builtin_bit_cast(float, (uint32_t)(127 + k) << 23);
+}
+
 __global__ void scale_table_kernel(const float* __restrict__ x_stat, int64_t c_in,
                                    const float* __restrict__ alpha, int n_alpha,
-                                   float* __restrict__ s_table, float* __restrict__ inv_table) {
+                                   float* __restrict__ s_table, float* __restrict__ inv_table,
+                                   const uint32_t* __restrict__ xmax_bits) {
   const int64_t c = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
   const int k = blockIdx.y;
   if (c >= c_in || k >= n_alpha) return;
@@ -109,14 +115,90 @@ __global__ void scale_table_kernel(const float* __restrict__ x_stat, int64_t c_i
   xs = xs > kXstatFloor ? xs : kXstatFloor;  // also maps NaN to the floor
   const float s = (float)pow((double)xs, (double)alpha[k]);
   s_table[(int64_t)k * c_in + c] = s;
-  if (inv_table) inv_table[(int64_t)k * c_in + c] = (float)(1.0 / (double)s);
+  if (inv_table) inv_table[(int64_t)k * c_in + c] = (float)(pow2_shift(xmax_bits) / (double)s);
 }
 
 hipError_t launch_scale_table(const float* x_stat, int64_t c_in, const float* alpha, int n_alpha,
-                              float* s_table, float* inv_table, hipStream_t stream) {
+                              float* s_table, float* inv_table, const uint32_t* xmax_bits,
+                              hipStream_t stream) {
   ProfScope ps("scale_table", stream, 8.0 * (double)n_alpha * (double)c_in);
   dim3 grid((unsigned)ceil_div(c_in, 256), (unsigned)n_alpha);
-  scale_table_kernel<<<grid, 256, 0, stream>>>(x_stat, c_in, alpha, n_alpha, s_table, inv_table);
+  scale_table_kernel<<<grid, 256, 0, stream>>>(x_stat, c_in, alpha, n_alpha, s_table, inv_table, xmax_bits);
+  return hipGetLastError();
+}
+
+__global__ void recip_kernel(const float* __restrict__ s, int64_t n, const uint32_t* __restrict__ xmax_bits,
+                             float* __restrict__ inv) {
+  const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  if (i < n) inv[i] = (float)(pow2_shift(xmax_bits) / (double)s[i]);
+}
+
+hipError_t launch_recip(const float* s, int64_t c_in, const uint32_t* xmax_bits, float* inv,
+                        hipStream_t stream) {
+  recip_kernel<<<(unsigned)ceil_div(c_in, 256), 256, 0, stream>>>(s, c_in, xmax_bits, inv);
+  return hipGetLastError();
+}
+
+// ------------------------------------------------ bf16 activations -> fp16 operand
+__global__ void zero_u32_kernel(uint32_t* p) { *p = 0u; }
+
+// max over the tensor of the magnitude bits; for bf16 the integer order of the
+// magnitude bits is the order of the magnitudes, so an integer atomic max is exact
+// and order independent
+__global__ __launch_bounds__(256) void absmax_bits_kernel(const uint16_t* __restrict__ X, int64_t n_tok,
+                                                          int64_t c_in, int64_t ldx,
+                                                          uint32_t* __restrict__ out) {
+  const int64_t chunks = c_in / 8, total = n_tok * chunks;
+  uint32_t m = 0;
+  for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < total;
+       i += (int64_t)gridDim.x * blockDim.x) {
+    const uint4 v = *reinterpret_cast<const uint4*>(X + (i / chunks) * ldx + (i % chunks) * 8);
+    const uint32_t w[4] = {v.x, v.y, v.z, v.w};
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+      const uint32_t lo = w[j] & 0x7fffu, hi = (w[j] >> 16) & 0x7fffu;
+      m = m > lo ? m : lo;
+      m = m > hi ? m : hi;
+    }
+  }
+#pragma unroll
+  for (int off = 32; off >= 1; off >>= 1) {
+    const uint32_t o = __shfl_xor(m, off, 64);
+    m = m > o ? m : o;
+  }
+  if ((threadIdx.x & 63) == 0) atomicMax(out, m);
+}
+
+__global__ __launch_bounds__(256) void bf16_to_f16_kernel(const uint16_t* __restrict__ X, int64_t n_tok,
+                                                          int64_t c_in, int64_t ldx,
+                                                          const uint32_t* __restrict__ xmax_bits,
+                                                          uint16_t* __restrict__ Xh) {
+  const int64_t chunks = c_in / 8, total = n_tok * chunks;
+  const float scale = __builtin_bit_cast(float, (uint32_t)(127 - shift_from_bf16_bits(*xmax_bits)) << 23);
+  for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < total;
+       i += (int64_t)gridDim.x * blockDim.x) {
+    const int64_t r = i / chunks, c = (i % chunks) * 8;
+    const uint4 v = *reinterpret_cast<const uint4*>(X + r * ldx + c);
+    const uint32_t w[4] = {v.x, v.y, v.z, v.w};
+    uint32_t o[4];
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+      const float lo = BF16::to_float((uint16_t)w[j]) * scale, hi = BF16::to_float((uint16_t)(w[j] >> 16)) * scale;
+      o[j] = (uint32_t)F16::from_float(lo) | ((uint32_t)F16::from_float(hi) << 16);
+    }
+    *reinterpret_cast<uint4*>(Xh + r * c_in + c) = make_uint4(o[0], o[1], o[2], o[3]);
+  }
+}
+
+hipError_t launch_xprep(const void* X, int64_t n_tok, int64_t c_in, int64_t ldx, uint32_t* xmax_bits,
+                        void* Xh, hipStream_t stream) {
+  ProfScope ps("bf16_to_f16", stream, 6.0 * (double)n_tok * (double)c_in);
+  const int64_t total = n_tok * (c_in / 8);
+  const unsigned grid = (unsigned)(ceil_div(total, 256) < 4096 ? ceil_div(total, 256) : 4096);
+  zero_u32_kernel<<<1, 1, 0, stream>>>(xmax_bits);
+  absmax_bits_kernel<<<grid, 256, 0, stream>>>((const uint16_t*)X, n_tok, c_in, ldx, xmax_bits);
+  bf16_to_f16_kernel<<<grid, 256, 0, stream>>>((const uint16_t*)X, n_tok, c_in, ldx, xmax_bits,
+                                               (uint16_t*)Xh);
   return hipGetLastError();
 }
 

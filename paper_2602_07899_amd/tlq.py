@@ -57,7 +57,7 @@ _SIGNATURES = {
     "tlq_scale_search": (C.c_int, [_P, _I64, _I64, _I64, _P, _I64, _I64, _P, _I64, _P, _P, _I32,
                                    _PP, _P, _P, _P, _P, _P, _P, _SZ, _P]),
     "tlq_ref_output": (C.c_int, [_P, _I64, _I64, _I64, _P, _I64, _I64, _P, _I64, _PP, _P]),
-    "tlq_apply_best_workspace_bytes": (_SZ, [_I64, _I64, _PP]),
+    "tlq_apply_best_workspace_bytes": (_SZ, [_I64, _I64, _I64, _PP]),
     "tlq_apply_best": (C.c_int, [_P, _I64, _I64, _I64, _P, _I64, _I64, _P, _PP, _P, _I64, _P, _SZ, _P]),
     "tlq_profile_enable": (C.c_int, [C.c_int]),
     "tlq_profile_reset": (C.c_int, []),
@@ -183,14 +183,14 @@ def ref_output(X, W, Y, p):
     return Y
 
 
-def apply_best_workspace_bytes(c_in, c_out, p):
-    return lib().tlq_apply_best_workspace_bytes(c_in, c_out, C.byref(p))
+def apply_best_workspace_bytes(n_tok, c_in, c_out, p):
+    return lib().tlq_apply_best_workspace_bytes(n_tok, c_in, c_out, C.byref(p))
 
 
 def apply_best(X, W, s, p, X_next, workspace=None):
     n, ci = X.shape
     co = W.shape[0]
-    ws = workspace if workspace is not None else _ws(apply_best_workspace_bytes(ci, co, p), X)
+    ws = workspace if workspace is not None else _ws(apply_best_workspace_bytes(n, ci, co, p), X)
     _check(lib().tlq_apply_best(_ptr(X), n, ci, _ld(X), _ptr(W), co, _ld(W), _ptr(s), C.byref(p),
                                 _ptr(X_next), _ld(X_next), _ptr(ws), ws.numel(), _stream()),
            "tlq_apply_best")

@@ -104,5 +104,9 @@ def test_workspace_queries():
     bad = tlq.params(bits=1)
     assert q(256, 512, 512, 20, bad) == 0
     assert tlq.x_stat_workspace_bytes(256, 512) >= 2 * 512 * 8
-    assert tlq.apply_best_workspace_bytes(512, 512, p) >= 512 * 512 * 2
+    assert tlq.apply_best_workspace_bytes(256, 512, 512, p) >= 512 * 512 * 2
+    pb = tlq.params(x_dtype=tlq.BF16)
+    assert (tlq.apply_best_workspace_bytes(256, 512, 512, pb)
+            >= tlq.apply_best_workspace_bytes(256, 512, 512, p) + 256 * 512 * 2)
+    assert q(256, 512, 512, 20, pb) >= small + 256 * 512 * 2
     assert tlq.weighted_layer_err_workspace_bytes(256, 512, 512, p) >= 512 * 512 * 2

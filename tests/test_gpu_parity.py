@@ -318,6 +318,27 @@ def test_scale_search_ragged_multi_tile(gpu, n, ci, co, bits, group, bf16):
     assert np.array_equal(best, st[idx])
 
 
+def test_scale_search_bf16_beyond_fp16_range(gpu):
+    """bf16 activations far outside the fp16 range: the library re-expresses them in
+    fp16 with a power-of-two prescale, so the loss accuracy must be that of fp16."""
+    rng = np.random.default_rng(77)
+    n, ci, co = 515, 512, 300
+    X = rng.standard_normal((n, ci)).astype(np.float32) * 3.0e4
+    X[:, rng.choice(ci, 5, replace=False)] *= 40.0            # up to ~5e6
+    W = (rng.standard_normal((co, ci)) * 0.02).astype(np.float32)
+    X, W = as_bf16_values(X), as_bf16_values(W)
+    w = rng.uniform(0.1, 1.0, n)
+    w = (w / w.sum()).astype(np.float32)
+    Y = orc.ref_output(X, W).astype(np.float32)
+    al = wl.alpha_grid(8)
+    p = tlq.params(bits=4, group=128, x_dtype=tlq.BF16, yref_dtype=tlq.F32)
+    best, idx, losses, st = run_search(gpu, X, W, Y, w, al, p, bf16=True)
+    ref = orc.scale_search(X, W, Y, w, 4, 128, al)
+    worst = check_losses(losses, ref["losses"], idx, "bf16 large")
+    print(f"bf16 |x| up to {np.abs(X).max():.3g}: max rel loss error {worst:.2e}")
+    assert worst < 5e-4      # fp16-class accuracy (an 8-bit operand would sit near 1e-2 here)
+
+
 def test_scale_search_with_supplied_x_stat_and_nonfinite(gpu):
     c = wl.CONFIGS["cfg1_small"]
     X, W, w = wl.make_tokens(c, 0), wl.make_weight(c, 0), wl.make_token_weights(c, 0)
