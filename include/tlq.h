@@ -161,6 +161,18 @@ tlq_status tlq_apply_best(const void* X, int64_t n_tok, int64_t c_in, int64_t ld
                           const tlq_params* p, void* X_next, int64_t ld_next,
                           void* workspace, size_t workspace_bytes, void* stream);
 
+/* ---- glue of the synthetic sequential chain (not the paper's method):
+ * builds the exposed input of the next linear from the quantised output of the
+ * previous one (Sec. 3.2.1 PassAct2 propagation).
+ *   v = Z (or Z*Zb elementwise when Zb != NULL);
+ *   X_out[t,c] = round16( v[t,c] / sqrt(mean_c v[t,:]^2 + 1e-6) * m(t)[c] ),
+ *   m(t) = m_a if period == 0 or (t mod period) < split, else m_b; NULL = ones.
+ * Z, Zb, X_out: [n_tok, c] x_dtype; m_a, m_b: float [c].  float arithmetic. */
+tlq_status tlq_rmsnorm_mul(const void* Z, int64_t n_tok, int64_t c, int64_t ldz, const void* Zb,
+                           int64_t ldzb, const float* m_a, const float* m_b, int32_t period,
+                           int32_t split, const tlq_params* p, void* X_out, int64_t ld_out,
+                           void* stream);
+
 /* ---- optional per-kernel timing (host-side bookkeeping only).
  * While enabled, every kernel the library launches is bracketed by HIP events
  * on the launch stream.  tlq_profile_collect waits for the recorded events

@@ -337,4 +337,19 @@ tlq_status tlq_apply_best(const void* X, int64_t n_tok, int64_t c_in, int64_t ld
   return hip_status(launch_gemm_store(g, st));
 }
 
+// ------------------------------------------------------------ chain glue
+tlq_status tlq_rmsnorm_mul(const void* Z, int64_t n_tok, int64_t c, int64_t ldz, const void* Zb,
+                           int64_t ldzb, const float* m_a, const float* m_b, int32_t period,
+                           int32_t split, const tlq_params* p, void* X_out, int64_t ld_out,
+                           void* stream) {
+  if (!Z || !X_out) return TLQ_ERR_NULL;
+  TLQ_TRY(check_params(p));
+  if (!dims_ok(n_tok, c, ldz) || ld_out < c || (Zb && ldzb < c)) return TLQ_ERR_SHAPE;
+  if (period < 0 || split < 0 || (period > 0 && split > period) || (period > 0 && (!m_a || !m_b)))
+    return TLQ_ERR_SHAPE;
+  if (!aligned(Z, 2) || !aligned(X_out, 2)) return TLQ_ERR_ALIGN;
+  return hip_status(launch_rmsnorm_mul(Z, ldz, Zb, ldzb, n_tok, c, p->x_dtype == TLQ_BF16, m_a, m_b,
+                                       period, split, X_out, ld_out, (hipStream_t)stream));
+}
+
 }  // extern "C"

@@ -117,4 +117,10 @@ hipError_t launch_finalize(const float* partial, int n_cand, int64_t tiles_per_c
 hipError_t launch_token_err_reduce(const float* tok_partial, int64_t tiles_o, int64_t n_tok,
                                    int64_t c_out, float* per_token_err, hipStream_t stream);
 
+
+// chain glue (glue.hip)
+hipError_t launch_rmsnorm_mul(const void* Z, int64_t ldz, const void* Zb, int64_t ldzb, int64_t n_tok,
+                              int64_t c, bool bf16, const float* m_a, const float* m_b, int period,
+                              int split, void* out, int64_t ldo, hipStream_t stream);
+
 }  // namespace tlq

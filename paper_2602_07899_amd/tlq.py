@@ -59,6 +59,7 @@ _SIGNATURES = {
     "tlq_ref_output": (C.c_int, [_P, _I64, _I64, _I64, _P, _I64, _I64, _P, _I64, _PP, _P]),
     "tlq_apply_best_workspace_bytes": (_SZ, [_I64, _I64, _I64, _PP]),
     "tlq_apply_best": (C.c_int, [_P, _I64, _I64, _I64, _P, _I64, _I64, _P, _PP, _P, _I64, _P, _SZ, _P]),
+    "tlq_rmsnorm_mul": (C.c_int, [_P, _I64, _I64, _I64, _P, _I64, _P, _P, _I32, _I32, _PP, _P, _I64, _P]),
     "tlq_profile_enable": (C.c_int, [C.c_int]),
     "tlq_profile_reset": (C.c_int, []),
     "tlq_profile_collect": (C.c_int, []),
@@ -195,6 +196,14 @@ def apply_best(X, W, s, p, X_next, workspace=None):
                                 _ptr(X_next), _ld(X_next), _ptr(ws), ws.numel(), _stream()),
            "tlq_apply_best")
     return X_next
+
+
+def rmsnorm_mul(Z, p, X_out, Zb=None, m_a=None, m_b=None, period=0, split=0):
+    n, c = Z.shape
+    _check(lib().tlq_rmsnorm_mul(_ptr(Z), n, c, _ld(Z), _ptr(Zb), 0 if Zb is None else _ld(Zb), _ptr(m_a),
+                                 _ptr(m_b), period, split, C.byref(p), _ptr(X_out), _ld(X_out), _stream()),
+           "tlq_rmsnorm_mul")
+    return X_out
 
 
 # ------------------------------------------------------------------ profiling

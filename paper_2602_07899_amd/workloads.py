@@ -79,6 +79,13 @@ CONFIGS = {
     "cfg2_7b_w4": Workload("cfg2_7b_w4", LLAMA7B, n_samples=16, n_vis=576, n_txt=64, bits=4),
     # same shapes, W3, 64 samples
     "cfg3_7b_w3": Workload("cfg3_7b_w3", LLAMA7B, n_samples=64, n_vis=576, n_txt=64, bits=3),
+    # scaled-down 7-linear chain (hidden 512, ffn 1408) for full-oracle parity of the
+    # quantisation-exposed sequential calibration
+    "cfg3_mini_w3": Workload("cfg3_mini_w3", (LinearSpec("q_proj", 512, 512), LinearSpec("k_proj", 512, 512),
+                                              LinearSpec("v_proj", 512, 512), LinearSpec("o_proj", 512, 512),
+                                              LinearSpec("gate_proj", 1408, 512), LinearSpec("up_proj", 1408, 512),
+                                              LinearSpec("down_proj", 512, 1408)),
+                             n_samples=5, n_vis=96, n_txt=32, bits=3, n_alpha=8, n_outlier=5),
     # 13B-class shapes, 128 samples x 1200 tokens
     "cfg4_13b_w4": Workload("cfg4_13b_w4", LLAMA13B, n_samples=128, n_vis=1152, n_txt=48, bits=4),
 }
@@ -137,6 +144,18 @@ def make_token_weights(wl: Workload, lin_idx: int) -> np.ndarray:
             w[b, wl.n_vis:] = 4.0 * g.lognormal(0.0, 1.0, wl.n_txt)
     w = w.reshape(-1)
     return (w / w.sum()).astype(np.float32)
+
+
+def chain_multipliers(wl: Workload, lin_idx: int) -> tuple:
+    """Per-channel multipliers (visual rows, text rows) that re-impose the outlier
+    channels on the exposed input of linear `lin_idx` in the sequential chain."""
+    c_in = wl.linears[lin_idx].c_in
+    mv = np.ones(c_in, dtype=np.float32)
+    mt = np.ones(c_in, dtype=np.float32)
+    oc = outlier_channels(wl, lin_idx)
+    mv[oc] = wl.vis_mult
+    mt[oc] = wl.txt_mult
+    return mv, mt
 
 
 def token_rows(wl: Workload, rows) -> tuple:

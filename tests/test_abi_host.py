@@ -91,6 +91,9 @@ def test_other_entry_points_reject_bad_arguments():
     assert l.tlq_apply_best(FAKE, 4, 128, 128, FAKE, 4, 128, FAKE, bp, FAKE, 8, FAKE, 8,
                             None) == tlq.ERR_WORKSPACE
     assert l.tlq_profile_get(99, None, 0, None, None, None) == tlq.ERR_SHAPE
+    assert l.tlq_rmsnorm_mul(None, 4, 8, 8, None, 0, None, None, 0, 0, bp, FAKE, 8, None) == tlq.ERR_NULL
+    assert l.tlq_rmsnorm_mul(FAKE, 4, 8, 8, None, 0, None, None, 0, 0, bp, FAKE, 4, None) == tlq.ERR_SHAPE
+    assert l.tlq_rmsnorm_mul(FAKE, 4, 8, 8, None, 0, None, None, 4, 2, bp, FAKE, 8, None) == tlq.ERR_SHAPE
 
 
 def test_workspace_queries():
