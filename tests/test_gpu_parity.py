@@ -419,3 +419,57 @@ def test_full_size_7b_linear_sampled_parity(gpu):
         assert abs(host(loss)[0] - losses[k]) / losses[k] < 1e-4
     # the losses are a proper objective: all finite and positive, minimum at idx
     assert np.all(np.isfinite(losses)) and np.all(losses > 0) and idx == int(np.argmin(losses))
+
+
+def test_full_size_13b_linear_sampled_parity(gpu):
+    """q_proj-shaped linear of the 13B workload at its real size (128 x 1200 = 153,600
+    tokens, 5120 x 5120, W4 g128, 20 candidates).  A full oracle would take hours, so
+    the oracle evaluates 48 sampled tokens (regenerated from the per-sample input
+    generators) for several candidates, and the search's losses are tied to the
+    single-candidate entry point that produced those per-token errors."""
+    import torch
+    c = wl.CONFIGS["cfg4_13b_w4"]
+    li = 0
+    spec = c.linears[li]
+    per = c.n_vis + c.n_txt
+    W = wl.make_weight(c, li)
+    w = wl.make_token_weights(c, li)
+    tX = torch.empty((c.n_tok, spec.c_in), dtype=torch.float16, device=gpu)
+    xsum = np.zeros(spec.c_in, np.float64)           # oracle-side statistic, accumulated per sample
+    for b in range(c.n_samples):
+        xb = wl.make_sample_tokens(c, li, b).astype(np.float16)
+        xsum += np.abs(xb.astype(np.float64)).sum(axis=0)
+        tX[b * per:(b + 1) * per] = torch.from_numpy(xb).to(gpu)
+    x_stat = (xsum / c.n_tok).astype(np.float32)     # same definition as orc.x_stat_mean, streamed
+    al = wl.alpha_grid(c.n_alpha)
+    ost = orc.scale_table(x_stat, al)
+    p = tlq.params(bits=c.bits, group=c.group)
+    tW, tw, tal = dev(W, gpu), dev(w, gpu), dev(al, gpu)
+    tY = torch.empty((c.n_tok, spec.c_out), dtype=torch.float16, device=gpu)
+    tlq.ref_output(tX, tW, tY, p)
+    best = empty((spec.c_in,), torch.float32, gpu)
+    idx = empty((1,), torch.int32, gpu)
+    losses = empty((c.n_alpha,), torch.float32, gpu)
+    st = empty((c.n_alpha, spec.c_in), torch.float32, gpu)
+    tlq.scale_search(tX, tW, tY, tw, tal, p, best, idx, losses, s_table_out=st)
+    torch.cuda.synchronize()
+    L = host(losses)
+    ulp = np.abs(host(st).view(np.int32).astype(np.int64) - ost.view(np.int32))
+    assert ulp.max() <= 1
+    assert np.all(np.isfinite(L)) and np.all(L > 0) and int(idx.item()) == int(np.argmin(L))
+    print(f"13B q_proj: best alpha index {int(idx.item())}, {int((ulp > 0).sum())} scale entries off by one ulp")
+    rows = np.sort(np.random.default_rng(2).choice(c.n_tok, 48, replace=False))
+    Xr = wl.make_token_subset(c, li, rows)
+    assert np.array_equal(Xr, host(tX[torch.from_numpy(rows).to(gpu)]))     # generator round trip
+    Yr = orc.ref_output(Xr, W).astype(np.float16)
+    wdq = torch.empty_like(tW)
+    loss = empty((1,), torch.float32, gpu)
+    pte = empty((c.n_tok,), torch.float32, gpu)
+    for k in (0, int(idx.item()), 19):
+        tlq.fake_quant(tW, dev(ost[k], gpu), p, Wdq=wdq)
+        inv = (1.0 / ost[k].astype(np.float64)).astype(np.float32)
+        tlq.weighted_layer_err(tX, wdq, dev(inv, gpu), tY, tw, p, loss, pte)
+        _, _, _, deq = orc.fake_quant(W, ost[k], c.bits, c.group)
+        e = orc.per_token_err(Yr, orc.quantised_output(Xr, deq.astype(np.float16), inv_s=inv))
+        np.testing.assert_allclose(host(pte)[rows], e, rtol=LOSS_RTOL)
+        assert abs(host(loss)[0] - L[k]) / L[k] < 2e-4
