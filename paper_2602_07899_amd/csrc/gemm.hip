@@ -100,6 +100,48 @@ __device__ __forceinline__ void store_y1(void* Y, int odt, int64_t idx, float y)
 }
 
 
+
+// Per-lane part of the loss of one wave tile whose first output row is `ow` and first
+// token is `tw`: sq[j] = sum over this lane's rows of (Y_ref - acc)^2 for its token of
+// fragment column j; part = sum_j token_w * sq[j].  YDT >= 0 fixes the Y_ref type at
+// compile time; FULL promises that the whole wave tile lies inside the matrix.
+template <int YDT, bool FULL, int FA, int FB>
+__device__ __forceinline__ void loss_rows(const GemmDev& a, f32x16 (&acc)[FA][FB], int64_t ow, int64_t tw,
+                                          float (&sq)[FB], float& part) {
+  const int lane = threadIdx.x & 63, frow = lane & 31, fhi = lane >> 5;
+  const int ydt = YDT >= 0 ? YDT : a.ydt;
+#pragma unroll
+  for (int j = 0; j < FB; ++j) {
+    const int64_t t = tw + j * 32 + frow;
+    float sumsq = 0.0f;
+    if (FULL || t < a.n_tok) {
+#pragma unroll
+      for (int i = 0; i < FA; ++i)
+#pragma unroll
+        for (int q = 0; q < 4; ++q) {
+          const int64_t o = ow + i * 32 + q * 8 + fhi * 4;
+          if (FULL || o + 3 < a.c_out) {
+            float y[4];
+            load_y4(a.Yref, ydt, t * a.ldy + o, y);
+#pragma unroll
+            for (int r = 0; r < 4; ++r) {
+              const float d = y[r] - acc[i][j][q * 4 + r];
+              sumsq += d * d;
+            }
+          } else {
+            for (int r = 0; r < 4; ++r)
+              if (o + r < a.c_out) {
+                const float d = load_y(a.Yref, ydt, t * a.ldy + o + r) - acc[i][j][q * 4 + r];
+                sumsq += d * d;
+              }
+          }
+        }
+      part += a.token_w[t] * sumsq;
+    }
+    sq[j] = sumsq;
+  }
+}
+
 // ---------------------------------------------------------------------------
 // Tile epilogue shared by both kernels.  Accumulator layout of a 32x32
 // fragment: lane holds column (lane%32) and rows 8*(v/4) + 4*(lane/32) + v%4,
@@ -133,38 +175,19 @@ __device__ __forceinline__ void tile_epilogue(const GemmDev& a, f32x16 (&acc)[FA
     }
     return;
   }
+  // Interior tiles (the common case) take a branch-free body specialised on the Y_ref
+  // type; edge tiles and odd strides take the guarded one.
   float part = 0.0f;
+  float sq[FB];
+  const bool interior = (o0 + NWO * WO <= a.c_out) && (t0 + BT <= a.n_tok);
+  if (interior && a.ydt == TLQ_F16) loss_rows<TLQ_F16, true, FA, FB>(a, acc, o0 + wo * WO, t0 + wt * WT, sq, part);
+  else if (interior && a.ydt == TLQ_F32) loss_rows<TLQ_F32, true, FA, FB>(a, acc, o0 + wo * WO, t0 + wt * WT, sq, part);
+  else if (interior) loss_rows<TLQ_BF16, true, FA, FB>(a, acc, o0 + wo * WO, t0 + wt * WT, sq, part);
+  else loss_rows<-1, false, FA, FB>(a, acc, o0 + wo * WO, t0 + wt * WT, sq, part);
+  if (EPI == EPI_LOSS_TOK) {
 #pragma unroll
-  for (int j = 0; j < FB; ++j) {
-    const int64_t t = t0 + wt * WT + j * 32 + frow;
-    const bool tok = t < a.n_tok;
-    float sumsq = 0.0f;
-    if (tok) {
-#pragma unroll
-      for (int i = 0; i < FA; ++i)
-#pragma unroll
-        for (int q = 0; q < 4; ++q) {
-          const int64_t o = o0 + wo * WO + i * 32 + q * 8 + fhi * 4;
-          if (o + 3 < a.c_out) {
-            float y[4];
-            load_y4(a.Yref, a.ydt, t * a.ldy + o, y);
-#pragma unroll
-            for (int r = 0; r < 4; ++r) {
-              const float d = y[r] - acc[i][j][q * 4 + r];
-              sumsq += d * d;
-            }
-          } else {
-            for (int r = 0; r < 4; ++r)
-              if (o + r < a.c_out) {
-                const float d = load_y(a.Yref, a.ydt, t * a.ldy + o + r) - acc[i][j][q * 4 + r];
-                sumsq += d * d;
-              }
-          }
-        }
-      part += a.token_w[t] * sumsq;
-    }
-    if (EPI == EPI_LOSS_TOK) {
-      const float both = sumsq + __shfl_xor(sumsq, 32, 64);
+    for (int j = 0; j < FB; ++j) {
+      const float both = sq[j] + __shfl_xor(sq[j], 32, 64);
       if (fhi == 0) rows[wo * BT + wt * WT + j * 32 + frow] = both;
     }
   }
