@@ -39,16 +39,28 @@ __device__ __forceinline__ void grid_params(float mx, float mn, const QuantDev& 
   }
 }
 
+// rint(fl(ws / delta)) without a division per element.  With r = fl(1/delta),
+// t = fl(ws * r) lies within 3 * 2^-24 * |Q| of the correctly rounded quotient q of
+// Q = ws/delta, so rint(t) == rint(q) unless a half-integer sits inside that gap.  When t is
+// that close to a half-integer (about one element in 10^5) the true division decides.
+__device__ __forceinline__ float rint_quotient(float ws, float delta, float rdelta) {
+  const float t = ws * rdelta;
+  float n = rintf(t);
+  const float gap = 0.5f - fabsf(t - n);                  // distance of t to the nearest tie
+  if (!(gap > fabsf(t) * 4.8e-7f + 2.4e-7f)) n = rintf(ws / delta);   // also taken for NaN/inf
+  return n;
+}
+
 template <bool SYM>
-__device__ __forceinline__ void quant_one(float ws, float delta, float zpf, const QuantDev& a,
-                                          float& code, float& deq) {
+__device__ __forceinline__ void quant_one(float ws, float delta, float rdelta, float zpf,
+                                          const QuantDev& a, float& code, float& deq) {
   if (!SYM) {
-    float q = rintf(ws / delta) + zpf;
+    float q = rint_quotient(ws, delta, rdelta) + zpf;
     q = fminf(fmaxf(q, 0.0f), a.qmax);
     code = q;
     deq = (q - zpf) * delta;
   } else {
-    float q = rintf(ws / delta);
+    float q = rint_quotient(ws, delta, rdelta);
     q = fminf(fmaxf(q, a.qlo), a.qhi);
     code = q + zpf;
     deq = q * delta;
@@ -59,7 +71,9 @@ __device__ __forceinline__ void quant_one(float ws, float delta, float zpf, cons
 // input channels; a group is `group/8` adjacent lanes; a wave covers 512
 // channels of one output row.  Min/max go through a butterfly inside the
 // lane group; W stays in registers while the candidates are looped over.
-template <typename T, bool SYM>
+// AUX = false drops the single-candidate outputs (codes, zero points, steps, dequantised
+// weights) at compile time: the search only needs the folded operands.
+template <typename T, bool SYM, bool AUX>
 __global__ __launch_bounds__(256) void quant_pow2_kernel(QuantDev a) {
   const int lane = threadIdx.x & 63;
   const int64_t wave = (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6);
@@ -115,23 +129,26 @@ __global__ __launch_bounds__(256) void quant_pow2_kernel(QuantDev a) {
     }
     float delta, zpf;
     grid_params<SYM>(mx, mn, a, delta, zpf);
+    const float rdelta = 1.0f / delta;
 
     uint32_t cw[2] = {0, 0};
     uint32_t hw[4] = {0, 0, 0, 0}, dw[4] = {0, 0, 0, 0};
 #pragma unroll
     for (int j = 0; j < 8; ++j) {
       float code, deq;
-      quant_one<SYM>(ws[j], delta, zpf, a, code, deq);
-      cw[j >> 2] |= ((uint32_t)code & 0xffu) << ((j & 3) * 8);
+      quant_one<SYM>(ws[j], delta, rdelta, zpf, a, code, deq);
       const float folded = deq * inv[j];
       hw[j >> 1] |= (uint32_t)(a.what_f16 ? F16::from_float(folded) : T::from_float(folded)) << ((j & 1) * 16);
-      dw[j >> 1] |= (uint32_t)T::from_float(deq) << ((j & 1) * 16);
+      if (AUX) {
+        cw[j >> 2] |= ((uint32_t)code & 0xffu) << ((j & 3) * 8);
+        dw[j >> 1] |= (uint32_t)T::from_float(deq) << ((j & 1) * 16);
+      }
     }
     if (!active) continue;
     if (a.what)
       *reinterpret_cast<uint4*>(a.what + (int64_t)k * a.what_cand_stride + row * a.c_in + c) =
           make_uint4(hw[0], hw[1], hw[2], hw[3]);
-    if (k == 0) {  // auxiliary outputs describe a single candidate
+    if (AUX && k == 0) {  // auxiliary outputs describe a single candidate
       if (a.codes) *reinterpret_cast<uint2*>(a.codes + row * a.c_in + c) = make_uint2(cw[0], cw[1]);
       if (a.wdq)
         *reinterpret_cast<uint4*>(a.wdq + row * a.ld_dq + c) = make_uint4(dw[0], dw[1], dw[2], dw[3]);
@@ -168,10 +185,11 @@ __global__ __launch_bounds__(256) void quant_any_kernel(QuantDev a) {
     }
     float delta, zpf;
     grid_params<SYM>(mx, mn, a, delta, zpf);
+    const float rdelta = 1.0f / delta;
     for (int64_t c = c0 + lane; c < c0 + a.group; c += 64) {
       const float ws = T::to_float(a.W[row * a.ldw + c]) * (sk ? sk[c] : 1.0f);
       float code, deq;
-      quant_one<SYM>(ws, delta, zpf, a, code, deq);
+      quant_one<SYM>(ws, delta, rdelta, zpf, a, code, deq);
       if (a.what)
         {
           const float folded = deq * (ik ? ik[c] : 1.0f);
@@ -208,10 +226,19 @@ hipError_t launch_fake_quant(const QuantArgs& q, hipStream_t stream) {
   if (pow2) {
     const int64_t waves = q.c_out * ceil_div(q.c_in, 512);
     const unsigned grid = (unsigned)ceil_div(waves, 4);
-    if (!q.bf16 && !sym) quant_pow2_kernel<F16, false><<<grid, 256, 0, stream>>>(d);
-    else if (!q.bf16) quant_pow2_kernel<F16, true><<<grid, 256, 0, stream>>>(d);
-    else if (!sym) quant_pow2_kernel<BF16, false><<<grid, 256, 0, stream>>>(d);
-    else quant_pow2_kernel<BF16, true><<<grid, 256, 0, stream>>>(d);
+    const bool aux = q.codes || q.zp || q.delta || q.wdq;
+    auto go = [&](auto kern) { kern<<<grid, 256, 0, stream>>>(d); };
+    if (aux) {
+      if (!q.bf16 && !sym) go(quant_pow2_kernel<F16, false, true>);
+      else if (!q.bf16) go(quant_pow2_kernel<F16, true, true>);
+      else if (!sym) go(quant_pow2_kernel<BF16, false, true>);
+      else go(quant_pow2_kernel<BF16, true, true>);
+    } else {
+      if (!q.bf16 && !sym) go(quant_pow2_kernel<F16, false, false>);
+      else if (!q.bf16) go(quant_pow2_kernel<F16, true, false>);
+      else if (!sym) go(quant_pow2_kernel<BF16, false, false>);
+      else go(quant_pow2_kernel<BF16, true, false>);
+    }
   } else {
     const int64_t waves = q.c_out * (q.c_in / d.group);
     const unsigned grid = (unsigned)ceil_div(waves, 4);
