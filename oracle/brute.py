@@ -107,3 +107,40 @@ def brute_search(X, W, Y_ref, token_w, bits, group, alphas):
         if losses[k] < losses[best]:
             best = k
     return xs, losses, best
+
+
+def brute_act_quant_row(xrow, s, act_bits):
+    """Per-token symmetric quantiser on x/s (Sec. 2.2 first two equations applied to one
+    activation row; Sec. 3.2.1 Q_a).  Returns (codes, sigma)."""
+    half = 1 << (act_bits - 1)
+    xt = [f32(f32(xrow[c]) * f32(1.0 / float(f32(s[c])))) for c in range(len(xrow))]
+    amax = f32(0.0)
+    for v in xt:
+        a = f32(abs(v))
+        if a > amax:
+            amax = a
+    if amax < f32(1e-5):
+        amax = f32(1e-5)
+    sigma = f32(amax / f32(half - 1))
+    codes = []
+    for v in xt:
+        q = _rne(float(f32(v / sigma)))
+        codes.append(int(min(max(q, -half), half - 1)))
+    return codes, sigma
+
+
+def brute_loss_aq(X, W, Y_ref, token_w, s, bits, group, act_bits):
+    n, c_in, c_out = len(X), len(X[0]), len(W)
+    deq_rows = [brute_fake_quant_row(W[o], s, bits, group)[3] for o in range(c_out)]
+    total = 0.0
+    for t in range(n):
+        codes, sigma = brute_act_quant_row(X[t], s, act_bits)
+        row = 0.0
+        for o in range(c_out):
+            y = 0.0
+            for c in range(c_in):
+                y += codes[c] * float(deq_rows[o][c])
+            d = float(Y_ref[t][o]) - float(sigma) * y
+            row += d * d
+        total += float(token_w[t]) * (row / c_out)
+    return total

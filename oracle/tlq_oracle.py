@@ -40,6 +40,8 @@ notes of the repository):
   - W is [C_out, C_in]; scale multiplies columns of W and divides columns of X.
   - ties between candidates resolve to the smallest alpha; a candidate whose
     loss is not finite is reported as +inf and never selected.
+  - activation quantisation (act_bits > 0): x/scale is formed in float32 as
+    x * float32(1/scale), the per-token step uses max|.| floored at 1e-5.
 
 Parity pins (see tests/test_oracle_pins.py): brute force on tiny layers
 (oracle/brute.py), hand-worked quantiser example (tests/golden), alpha=0 and
@@ -169,6 +171,41 @@ def requantise_on_grid(values, delta, zp, bits, group):
 
 
 # --------------------------------------------------------------------------
+# Q_a  per-token symmetric activation fake quantisation
+# --------------------------------------------------------------------------
+def recip_scale(s):
+    """float32( 1 / float64(s) ): the reciprocal both sides multiply by."""
+    return (1.0 / np.asarray(s, np.float32).astype(np.float64)).astype(np.float32)
+
+
+def act_quant(X, inv_s, act_bits):
+    """Q_a(x / scale) of Sec. 3.2.1 with the symmetric per-token quantiser of
+    Sec. 2.2 (first two equations, X = activations, one step per token row):
+        xt      = float32(X) * inv_s                    (float32, one rounding)
+        sigma_t = max(max_c |xt[t,c]|, 1e-5) / (2**(n-1) - 1)
+        code    = clip(rint(xt / sigma_t), -2**(n-1), 2**(n-1) - 1)
+        xhat    = code * sigma_t
+    inv_s is the float32 reciprocal of the channel scale (None = ones).  All grid
+    arithmetic is float32, one rounding per operation, round-half-to-even.
+    Returns codes int16 [N, C], sigma float32 [N]."""
+    xt = np.asarray(X).astype(np.float32)
+    if inv_s is not None:
+        xt = xt * np.asarray(inv_s, np.float32)[None, :]
+    half = 2 ** (act_bits - 1)
+    amax = np.maximum(np.abs(xt).max(axis=1), RANGE_FLOOR)
+    sigma = (amax / _F32(half - 1)).astype(np.float32)
+    codes = np.clip(np.rint(xt / sigma[:, None]), _F32(-half), _F32(half - 1))
+    return codes.astype(np.int16), sigma
+
+
+def quantised_output_aq(X, deq, s, act_bits):
+    """f_q with activation quantisation, bias-free, float64:
+    Yq[t,o] = sigma_t * sum_c code[t,c] * deq[o,c]   (Sec. 3.2.1 f_q)."""
+    codes, sigma = act_quant(X, None if s is None else recip_scale(s), act_bits)
+    return (codes.astype(np.float64) @ to_f64(deq).T) * sigma.astype(np.float64)[:, None]
+
+
+# --------------------------------------------------------------------------
 # S3 / S4  quantised layer output and the weighted objective
 # --------------------------------------------------------------------------
 def ref_output(X, W):
@@ -215,7 +252,7 @@ def select_best(losses):
 
 
 def scale_search(X, W, Y_ref, token_w, bits, group, alpha_grid,
-                 x_stat=None, s_table=None, symmetric=False):
+                 x_stat=None, s_table=None, symmetric=False, act_bits=0):
     """Exhaustive search over the alpha grid (Sec. 3.2.1).
 
     Returns dict with s_table [A, C_in] f32, losses [A] f64 (+inf where not
@@ -230,7 +267,11 @@ def scale_search(X, W, Y_ref, token_w, bits, group, alpha_grid,
     losses = np.empty(A, dtype=np.float64)
     for k in range(A):
         _, _, _, deq = fake_quant(W, s_table[k], bits, group, symmetric=symmetric)
-        L, _ = weighted_layer_err(X, deq, Y_ref, token_w, s=s_table[k])
+        if act_bits:
+            e = per_token_err(Y_ref, quantised_output_aq(X, deq, s_table[k], act_bits))
+            L = float((to_f64(token_w) * e).sum())
+        else:
+            L, _ = weighted_layer_err(X, deq, Y_ref, token_w, s=s_table[k])
         losses[k] = L if np.isfinite(L) else np.inf
     best = select_best(losses)
     best_scales = s_table[best].copy() if best >= 0 else np.full(s_table.shape[1], np.nan, np.float32)
@@ -238,10 +279,12 @@ def scale_search(X, W, Y_ref, token_w, bits, group, alpha_grid,
             "best_idx": best, "best_scales": best_scales}
 
 
-def apply_best(X, W, s, bits, group, symmetric=False):
+def apply_best(X, W, s, bits, group, symmetric=False, act_bits=0):
     """PassAct2 input of the next layer: f_q(x; scale*) in float64
     (Sec. 3.2.1 PassAct2 equation); the caller casts to its activation type."""
     _, _, _, deq = fake_quant(W, s, bits, group, symmetric=symmetric)
+    if act_bits:
+        return quantised_output_aq(X, deq, s, act_bits)
     return quantised_output(X, deq, s=s)
 
 

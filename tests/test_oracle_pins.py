@@ -330,3 +330,66 @@ def test_pins_catch_planted_mistakes():
     d = Y - xs_ok @ quant(W * s).astype(np.float64).T
     assert float((w[::-1] * (d * d).mean(axis=1)).sum()) != good   # weights on wrong tokens
     assert float((w * (d * d).sum(axis=1)).sum()) != good          # dropped the 1/C_out
+
+
+# ------------------------------------------------- activation quantisation (Q_a)
+def test_act_quant_closed_forms():
+    # Sec. 2.2: s_i = max_j |X_ij| / (2^(n-1) - 1), codes in [-2^(n-1), 2^(n-1) - 1]
+    X = wl.make_tokens(wl.CONFIGS["cfg1_small"], 0)
+    for bits in (8, 6, 4):
+        half = 2 ** (bits - 1)
+        codes, sigma = orc.act_quant(X, None, bits)
+        am = np.abs(X.astype(np.float32)).max(axis=1)
+        assert np.array_equal(sigma, am / np.float32(half - 1))
+        assert codes.min() >= -half and codes.max() <= half - 1
+        assert np.all(np.abs(codes).max(axis=1) == half - 1)        # the row maximum lands on the top code
+        xhat = codes.astype(np.float64) * sigma.astype(np.float64)[:, None]
+        assert np.all(np.abs(xhat - X.astype(np.float64)) <= 0.5 * sigma[:, None] * (1 + 1e-4))
+        # idempotent: quantising the dequantised row again gives the same codes and step
+        c2, s2 = orc.act_quant(xhat.astype(np.float32), None, bits)
+        assert np.array_equal(c2, codes) and np.allclose(s2, sigma, rtol=1e-6)
+    # int8 example worked by hand: row [1.27, -0.635, 0.0049, 0.02] -> step 0.01, codes 127, -64 (tie to even), 0, 2
+    Xh = np.array([[1.27, -0.64, 0.0049, 0.02]], np.float32)
+    c, sg = orc.act_quant(Xh, None, 8)
+    assert np.isclose(sg[0], 0.01, rtol=1e-6) and c[0].tolist() == [127, -64, 0, 2]
+    # a constant zero row takes the floored step and all-zero codes
+    c, sg = orc.act_quant(np.zeros((1, 8), np.float32), None, 8)
+    assert sg[0] == np.float32(1e-5) / np.float32(127) and not c.any()
+
+
+@pytest.mark.parametrize("seed,n,ci,co,bits,group,abits", [(1, 5, 8, 3, 4, 4, 8), (2, 6, 8, 4, 3, 2, 6),
+                                                          (3, 4, 4, 5, 4, 0, 4)])
+def test_act_quant_search_matches_brute_force(seed, n, ci, co, bits, group, abits):
+    X, W, w = wl.tiny_layer(seed, n, ci, co)
+    Y = orc.ref_output(X, W).astype(np.float32)
+    alphas = [0.0, 0.3, 0.6]
+    res = orc.scale_search(X, W, Y, w, bits, group, np.array(alphas, np.float32), act_bits=abits)
+    xs = brute.brute_x_stat(X.tolist())
+    for k, a in enumerate(alphas):
+        s_b = brute.brute_scale(xs, a)
+        Lb = brute.brute_loss_aq(X.tolist(), W.tolist(), Y.tolist(), w.tolist(), s_b, bits, group, abits)
+        np.testing.assert_allclose(res["losses"][k], Lb, rtol=1e-12)
+        codes, sigma = orc.act_quant(X, orc.recip_scale(res["s_table"][k]), abits)
+        for t in range(n):
+            cb, sb = brute.brute_act_quant_row(X[t].tolist(), s_b, abits)
+            assert cb == codes[t].tolist() and float(sb) == float(sigma[t])
+
+
+def test_act_quant_limits():
+    # many activation bits on a narrow row: Q_a is nearly the identity, so the loss approaches
+    # the weight-only loss; and the activation error adds to it at low bits
+    c = wl.CONFIGS["cfg1_small"]
+    X, W, w = wl.make_tokens(c, 0), wl.make_weight(c, 0), wl.make_token_weights(c, 0)
+    Y = orc.ref_output(X, W)
+    al = np.array([0.0, 0.5], np.float32)
+    base = orc.scale_search(X, W, Y, w, 4, 128, al)["losses"]
+    a8 = orc.scale_search(X, W, Y, w, 4, 128, al, act_bits=8)["losses"]
+    a4 = orc.scale_search(X, W, Y, w, 4, 128, al, act_bits=4)["losses"]
+    assert np.all(a8 > base * 0.98) and np.all(a4 > a8)
+    # smoothing (alpha = 0.5) shrinks the per-token range of the outlier rows: it helps A4 far more than A16
+    assert a4[1] / a4[0] < base[1] / base[0]
+    # exact representability: an integer-valued row whose max is 127 survives A8 unchanged
+    Xi = np.random.default_rng(0).integers(-127, 128, (4, 16)).astype(np.float32)
+    Xi[:, 0] = 127
+    codes, sigma = orc.act_quant(Xi, None, 8)
+    assert np.all(sigma == 1.0) and np.array_equal(codes, Xi.astype(np.int16))
