@@ -73,6 +73,9 @@ def main():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=5)
     ap.add_argument("--warmup", type=int, default=2)
+    ap.add_argument("--act-bits", type=int, default=0,
+                    help="also quantise activations per token inside every candidate (the paper's "
+                         "W4A8 / W4A6 objective); 0 = the weight-only headline workload")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-ceiling", action="store_true",
                     help="skip the register-only MFMA ceiling measurement (context only)")
@@ -93,7 +96,8 @@ def main():
         sys.exit(2)
     dev = torch.device("cuda:0")
     workload = wl.CONFIGS["cfg2_7b_w4"]
-    p = tlq.params(bits=workload.bits, group=workload.group, x_dtype=tlq.F16, yref_dtype=tlq.F16)
+    p = tlq.params(bits=workload.bits, group=workload.group, act_bits=args.act_bits, x_dtype=tlq.F16,
+                   yref_dtype=tlq.F16)
     al = torch.from_numpy(wl.alpha_grid(workload.n_alpha)).to(dev)
 
     # ---- inputs resident in HBM (Y_ref = f_fp output through the library's own GEMM)
@@ -148,7 +152,8 @@ def main():
         "data": "synthetic",
         "config": {"workload": workload.name, "linears": [f"{s.name}:{s.c_out}x{s.c_in}" for s in workload.linears],
                    "n_tok": workload.n_tok, "bits": workload.bits, "group": workload.group,
-                   "n_alpha": workload.n_alpha, "evals_per_step": len(layers) * workload.n_alpha},
+                   "n_alpha": workload.n_alpha, "evals_per_step": len(layers) * workload.n_alpha,
+                   "act_bits": args.act_bits},
         "fused_kernel_tflops": tflops, "pct_fp16_mfma_peak": 100.0 * tflops / PEAK_FP16_TFLOPS,
         "roofline": {"bound": "mfma", "kernel": "gemm_loss", "achieved": tflops, "peak": PEAK_FP16_TFLOPS,
                      "unit": "TFLOP/s", "frac": tflops / PEAK_FP16_TFLOPS,
@@ -162,7 +167,7 @@ def main():
     }
     if not args.no_ceiling:
         result["mfma_ceiling"] = mfma_ceiling()
-    if not args.no_cpu_baseline:
+    if not args.no_cpu_baseline and args.act_bits == 0:
         from oracle import tlq_oracle as orc
         result["cpu_baseline"] = cpu_baseline(wl, orc, workload)
     print(json.dumps(result))

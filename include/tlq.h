@@ -33,6 +33,11 @@
  *     and of `group` (TLQ_ERR_SHAPE otherwise).
  *   - Calls on different streams may run concurrently if their workspaces and
  *     outputs are disjoint.
+ *   - act_bits > 0 (Sec. 3.2.1 f_q with Q_a; quantiser of Sec. 2.2 per token row):
+ *     xt = x * float(1/s); sigma_t = max(max_c |xt|, 1e-5) / (2^(n-1)-1);
+ *     code = clip(rint(xt/sigma_t), -2^(n-1), 2^(n-1)-1); f_q = sigma_t * code . deq^T.
+ *     float arithmetic, round half to even.  Applies to tlq_scale_search,
+ *     tlq_weighted_layer_err and tlq_apply_best; needs c_in <= 16384.
  *   - x_dtype = BF16: inputs and 16-bit outputs are bf16.  Operands the library
  *     computes itself (the folded weights deq/s) are kept in fp16, and the tokens
  *     are re-expressed in fp16 in the workspace (exact for bf16 values after a
@@ -69,7 +74,7 @@ typedef struct tlq_params {
   int32_t bits;         /* weight bits, 2..8 */
   int32_t group;        /* input channels per quantisation group; 0 = whole row */
   int32_t symmetric;    /* 0 = asymmetric min/max grid, 1 = symmetric max|.| grid */
-  int32_t act_bits;     /* must be 0: activations are not quantised */
+  int32_t act_bits;     /* 0 = activations not quantised; 2..8 = per-token symmetric Q_a */
   int32_t xstat_kind;   /* 0 = mean |x| over tokens, 1 = max |x| over tokens */
   int32_t x_dtype;      /* tlq_dtype of X and of W and of the MFMA operands: F16 or BF16 */
   int32_t yref_dtype;   /* tlq_dtype of Y_ref (and of tlq_ref_output's result) */
@@ -111,6 +116,14 @@ tlq_status tlq_fake_quant(const void* W, int64_t c_out, int64_t c_in, int64_t ld
                           const float* s, const tlq_params* p,
                           uint8_t* codes, uint8_t* zp, float* delta,
                           void* Wdq, int64_t ld_dq, void* stream);
+
+/* ---- Q_a alone (Sec. 3.2.1 Q_a(x/scale); quantiser of Sec. 2.2 per token row; formula in
+ * the conventions above).  Needs act_bits > 0.  inv_s: float [c_in] or NULL (ones).
+ * codes: out [n_tok, c_in] dense, the integer codes stored as fp16 numbers (exact);
+ * sigma: out float [n_tok]. */
+tlq_status tlq_act_fake_quant(const void* X, int64_t n_tok, int64_t c_in, int64_t ldx,
+                              const float* inv_s, const tlq_params* p, void* codes, float* sigma,
+                              void* stream);
 
 /* ---- S3+S4 for one given dequantised weight matrix (Sec. 3.2.1 objective
  * with f_q = (X*inv_s) Wdq^T):

@@ -23,7 +23,7 @@ tlq_status check_params(const tlq_params* p) {
   if (p->bits < 2 || p->bits > 8) return TLQ_ERR_UNSUPPORTED;
   if (p->group < 0 || (p->group % 8) != 0) return TLQ_ERR_UNSUPPORTED;
   if (p->symmetric != 0 && p->symmetric != 1) return TLQ_ERR_UNSUPPORTED;
-  if (p->act_bits != 0) return TLQ_ERR_UNSUPPORTED;
+  if (p->act_bits != 0 && (p->act_bits < 2 || p->act_bits > 8)) return TLQ_ERR_UNSUPPORTED;
   if (p->xstat_kind != 0 && p->xstat_kind != 1) return TLQ_ERR_UNSUPPORTED;
   if (p->x_dtype != TLQ_F16 && p->x_dtype != TLQ_BF16) return TLQ_ERR_UNSUPPORTED;
   if (p->yref_dtype != TLQ_F16 && p->yref_dtype != TLQ_BF16 && p->yref_dtype != TLQ_F32)
@@ -58,11 +58,23 @@ tlq_status hip_status(hipError_t e) { return e == hipSuccess ? TLQ_OK : TLQ_ERR_
 // ---- workspace plans -----------------------------------------------------------
 // With bf16 inputs the computed operand is kept in fp16 and the tokens are re-expressed
 // exactly in fp16 (see launch_xprep): `xh` holds them, `xmax` the bits of max|X|.
+// With activation quantisation (act_bits > 0) every candidate has its own token matrix
+// (fp16 integer codes, `xc`, produced `act_batch` candidates at a time) and per-token
+// steps `sig`; the tokens themselves are never an MFMA operand, so `xh` is not needed.
+constexpr size_t kActBatchBytes = (size_t)8 << 30;
+int act_batch(int64_t n_tok, int64_t c_in, int n_alpha) {
+  const size_t per = (size_t)n_tok * c_in * 2;
+  size_t nb = kActBatchBytes / (per ? per : 1);
+  if (nb < 1) nb = 1;
+  return nb > (size_t)n_alpha ? n_alpha : (int)nb;
+}
 struct SearchPlan {
   double* xs_partial; float* x_stat; float* s_table; float* inv_table; float* partial;
-  uint16_t* what; uint32_t* xmax; uint16_t* xh; size_t bytes; int64_t tiles_o, tiles_t;
+  uint16_t* what; uint32_t* xmax; uint16_t* xh; float* sig; uint16_t* xc; int nb; size_t bytes;
+  int64_t tiles_o, tiles_t;
 };
-SearchPlan plan_search(void* ws, int64_t n_tok, int64_t c_in, int64_t c_out, int n_alpha, bool bf16) {
+SearchPlan plan_search(void* ws, int64_t n_tok, int64_t c_in, int64_t c_out, int n_alpha, bool bf16,
+                       bool act) {
   SearchPlan s;
   Carver c(ws);
   gemm_tile_counts(n_tok, c_out, &s.tiles_o, &s.tiles_t);
@@ -73,16 +85,19 @@ SearchPlan plan_search(void* ws, int64_t n_tok, int64_t c_in, int64_t c_out, int
   s.partial = c.take<float>((size_t)n_alpha * s.tiles_o * s.tiles_t);
   s.what = c.take<uint16_t>((size_t)n_alpha * c_out * c_in);
   s.xmax = c.take<uint32_t>(1);
-  s.xh = bf16 ? c.take<uint16_t>((size_t)n_tok * c_in) : nullptr;
+  s.xh = (bf16 && !act) ? c.take<uint16_t>((size_t)n_tok * c_in) : nullptr;
+  s.nb = act ? act_batch(n_tok, c_in, n_alpha) : 0;
+  s.sig = act ? c.take<float>((size_t)n_alpha * n_tok) : nullptr;
+  s.xc = act ? c.take<uint16_t>((size_t)s.nb * n_tok * c_in) : nullptr;
   s.bytes = c.off;
   return s;
 }
 
 struct ErrPlan {
-  float* partial; float* tok_partial; uint16_t* folded; uint32_t* xmax; uint16_t* xh; size_t bytes;
-  int64_t tiles_o, tiles_t;
+  float* partial; float* tok_partial; uint16_t* folded; uint32_t* xmax; uint16_t* xh; float* sig;
+  size_t bytes; int64_t tiles_o, tiles_t;   // xh doubles as the code matrix in act mode
 };
-ErrPlan plan_err(void* ws, int64_t n_tok, int64_t c_in, int64_t c_out, bool bf16) {
+ErrPlan plan_err(void* ws, int64_t n_tok, int64_t c_in, int64_t c_out, bool bf16, bool act) {
   ErrPlan e;
   Carver c(ws);
   gemm_tile_counts(n_tok, c_out, &e.tiles_o, &e.tiles_t);
@@ -90,7 +105,8 @@ ErrPlan plan_err(void* ws, int64_t n_tok, int64_t c_in, int64_t c_out, bool bf16
   e.tok_partial = c.take<float>((size_t)e.tiles_o * n_tok);
   e.folded = c.take<uint16_t>((size_t)c_out * c_in);
   e.xmax = c.take<uint32_t>(1);
-  e.xh = bf16 ? c.take<uint16_t>((size_t)n_tok * c_in) : nullptr;
+  e.xh = (bf16 || act) ? c.take<uint16_t>((size_t)n_tok * c_in) : nullptr;
+  e.sig = act ? c.take<float>((size_t)n_tok) : nullptr;
   e.bytes = c.off;
   return e;
 }
@@ -163,11 +179,25 @@ tlq_status tlq_fake_quant(const void* W, int64_t c_out, int64_t c_in, int64_t ld
   return hip_status(launch_fake_quant(q, (hipStream_t)stream));
 }
 
+// ------------------------------------------------------------------------ Q_a
+tlq_status tlq_act_fake_quant(const void* X, int64_t n_tok, int64_t c_in, int64_t ldx,
+                              const float* inv_s, const tlq_params* p, void* codes, float* sigma,
+                              void* stream) {
+  if (!X || !codes || !sigma) return TLQ_ERR_NULL;
+  TLQ_TRY(check_params(p));
+  if (p->act_bits == 0) return TLQ_ERR_UNSUPPORTED;
+  if (!dims_ok(n_tok, c_in, ldx) || (c_in % 8) != 0) return TLQ_ERR_SHAPE;
+  if (c_in > act_quant_max_cin()) return TLQ_ERR_UNSUPPORTED;
+  if (!mat16_aligned(X, ldx) || !aligned(codes, 16) || (inv_s && !aligned(inv_s, 4))) return TLQ_ERR_ALIGN;
+  return hip_status(launch_act_quant(X, n_tok, c_in, ldx, p->x_dtype == TLQ_BF16, inv_s, 0, 1,
+                                     p->act_bits, codes, sigma, (hipStream_t)stream));
+}
+
 // -------------------------------------------------------------------- S3 + S4
 size_t tlq_weighted_layer_err_workspace_bytes(int64_t n_tok, int64_t c_in, int64_t c_out,
                                               const tlq_params* p) {
   if (n_tok <= 0 || c_in <= 0 || c_out <= 0 || check_params(p) != TLQ_OK) return 0;
-  return plan_err(nullptr, n_tok, c_in, c_out, p->x_dtype == TLQ_BF16).bytes;
+  return plan_err(nullptr, n_tok, c_in, c_out, p->x_dtype == TLQ_BF16, p->act_bits != 0).bytes;
 }
 
 tlq_status tlq_weighted_layer_err(const void* X, int64_t n_tok, int64_t c_in, int64_t ldx,
@@ -187,11 +217,21 @@ tlq_status tlq_weighted_layer_err(const void* X, int64_t n_tok, int64_t c_in, in
                    tlq_weighted_layer_err_workspace_bytes(n_tok, c_in, c_out, p)));
   hipStream_t st = (hipStream_t)stream;
   const bool bf16 = p->x_dtype == TLQ_BF16;
-  ErrPlan e = plan_err(workspace, n_tok, c_in, c_out, bf16);
+  const bool act = p->act_bits != 0;
+  if (act && c_in > act_quant_max_cin()) return TLQ_ERR_UNSUPPORTED;
+  ErrPlan e = plan_err(workspace, n_tok, c_in, c_out, bf16, act);
   GemmArgs g{};
   g.X = X; g.n_tok = n_tok; g.c_in = c_in; g.ldx = ldx;
   g.Wh = Wdq; g.c_out = c_out; g.ldw = ldw; g.w_cand_stride = 0; g.n_cand = 1; g.bf16 = bf16;
-  if (inv_s) {
+  if (act) {
+    // Q_a(x * inv_s) as exact fp16 integer codes + per-token steps; the weights stay unfolded
+    TLQ_HIP(launch_act_quant(X, n_tok, c_in, ldx, bf16, inv_s, 0, 1, p->act_bits, e.xh, e.sig, st));
+    g.X = e.xh; g.ldx = c_in; g.tok_scale = e.sig; g.bf16 = false;
+    if (bf16) {
+      TLQ_HIP(launch_fold_scale(Wdq, c_out, c_in, ldw, true, nullptr, nullptr, true, e.folded, st));
+      g.Wh = e.folded; g.ldw = c_in;
+    }
+  } else if (inv_s) {
     // the folded operand is a computed value: with bf16 inputs keep it (and X) in fp16
     if (bf16) {
       TLQ_HIP(launch_xprep(X, n_tok, c_in, ldx, e.xmax, e.xh, st));
@@ -217,7 +257,7 @@ size_t tlq_scale_search_workspace_bytes(int64_t n_tok, int64_t c_in, int64_t c_o
   if (n_tok <= 0 || c_in <= 0 || c_out <= 0 || n_alpha <= 0 || n_alpha > TLQ_MAX_ALPHA ||
       check_params(p) != TLQ_OK)
     return 0;
-  return plan_search(nullptr, n_tok, c_in, c_out, n_alpha, p->x_dtype == TLQ_BF16).bytes;
+  return plan_search(nullptr, n_tok, c_in, c_out, n_alpha, p->x_dtype == TLQ_BF16, p->act_bits != 0).bytes;
 }
 
 tlq_status tlq_scale_search(const void* X, int64_t n_tok, int64_t c_in, int64_t ldx,
@@ -240,17 +280,19 @@ tlq_status tlq_scale_search(const void* X, int64_t n_tok, int64_t c_in, int64_t 
                    tlq_scale_search_workspace_bytes(n_tok, c_in, c_out, n_alpha, p)));
   hipStream_t st = (hipStream_t)stream;
   const bool bf16 = p->x_dtype == TLQ_BF16;
-  SearchPlan s = plan_search(workspace, n_tok, c_in, c_out, n_alpha, bf16);
+  const bool act = p->act_bits != 0;
+  if (act && c_in > act_quant_max_cin()) return TLQ_ERR_UNSUPPORTED;
+  SearchPlan s = plan_search(workspace, n_tok, c_in, c_out, n_alpha, bf16, act);
 
   const float* x_stat = x_stat_in;
   if (!x_stat) {  // S0
     TLQ_HIP(launch_xstat(X, n_tok, c_in, ldx, bf16, p->xstat_kind, s.xs_partial, s.x_stat, st));
     x_stat = s.x_stat;
   }
-  if (bf16) TLQ_HIP(launch_xprep(X, n_tok, c_in, ldx, s.xmax, s.xh, st));
+  if (bf16 && !act) TLQ_HIP(launch_xprep(X, n_tok, c_in, ldx, s.xmax, s.xh, st));
   // S1
   TLQ_HIP(launch_scale_table(x_stat, c_in, alpha_grid, n_alpha, s.s_table, s.inv_table,
-                             bf16 ? s.xmax : nullptr, st));
+                             (bf16 && !act) ? s.xmax : nullptr, st));
   if (s_table_out)
     TLQ_HIP(hipMemcpyAsync(s_table_out, s.s_table, (size_t)n_alpha * c_in * sizeof(float),
                            hipMemcpyDeviceToDevice, st));
@@ -258,7 +300,8 @@ tlq_status tlq_scale_search(const void* X, int64_t n_tok, int64_t c_in, int64_t 
   QuantArgs q{};
   q.W = W; q.c_out = c_out; q.c_in = c_in; q.ldw = ldw; q.bf16 = bf16;
   q.bits = p->bits; q.group = p->group; q.symmetric = p->symmetric;
-  q.s_table = s.s_table; q.inv_table = s.inv_table; q.n_cand = n_alpha;
+  // (with activation quantisation 1/s belongs to Q_a's argument, so the weights stay unfolded)
+  q.s_table = s.s_table; q.inv_table = act ? nullptr : s.inv_table; q.n_cand = n_alpha;
   q.what = s.what; q.what_cand_stride = c_out * c_in; q.what_f16 = true;
   TLQ_HIP(launch_fake_quant(q, st));
   // S3 + S4: one launch over the stacked candidates (fp16 operands in either case)
@@ -268,7 +311,24 @@ tlq_status tlq_scale_search(const void* X, int64_t n_tok, int64_t c_in, int64_t 
   g.n_cand = n_alpha; g.bf16 = false;
   g.Yref = Y_ref; g.ldy = ldy; g.yref_dtype = p->yref_dtype; g.token_w = token_w;
   g.partial = s.partial; g.tok_partial = nullptr;
-  TLQ_HIP(launch_gemm_loss(g, st));
+  if (!act) {
+    TLQ_HIP(launch_gemm_loss(g, st));
+  } else {
+    // Q_a(x / s_k) differs per candidate: quantise the tokens for a batch of candidates,
+    // contract each candidate with its own code matrix, scale by the per-token step
+    const int64_t tiles = s.tiles_o * s.tiles_t;
+    for (int k0 = 0; k0 < n_alpha; k0 += s.nb) {
+      const int nb = (n_alpha - k0) < s.nb ? (n_alpha - k0) : s.nb;
+      TLQ_HIP(launch_act_quant(X, n_tok, c_in, ldx, bf16, s.inv_table, k0, nb, p->act_bits, s.xc,
+                               s.sig + (size_t)k0 * n_tok, st));
+      GemmArgs b = g;
+      b.X = s.xc; b.ldx = c_in; b.x_cand_stride = n_tok * c_in;
+      b.tok_scale = s.sig + (size_t)k0 * n_tok;
+      b.Wh = s.what + (size_t)k0 * c_out * c_in; b.n_cand = nb;
+      b.partial = s.partial + (size_t)k0 * tiles;
+      TLQ_HIP(launch_gemm_loss(b, st));
+    }
+  }
   // S4 combine + S5
   TLQ_HIP(launch_finalize(s.partial, n_alpha, s.tiles_o * s.tiles_t, c_out, s.s_table, c_in, losses,
                           best_idx, best_scales, st));
@@ -298,8 +358,10 @@ tlq_status tlq_ref_output(const void* X, int64_t n_tok, int64_t c_in, int64_t ld
 size_t tlq_apply_best_workspace_bytes(int64_t n_tok, int64_t c_in, int64_t c_out,
                                       const tlq_params* p) {
   if (n_tok <= 0 || c_in <= 0 || c_out <= 0 || check_params(p) != TLQ_OK) return 0;
+  const bool xbuf = p->x_dtype == TLQ_BF16 || p->act_bits != 0;
   return align_up((size_t)c_in * sizeof(float), 256) + align_up((size_t)c_out * c_in * 2, 256) + 256 +
-         (p->x_dtype == TLQ_BF16 ? align_up((size_t)n_tok * c_in * 2, 256) : 0);
+         (xbuf ? align_up((size_t)n_tok * c_in * 2, 256) : 0) +
+         (p->act_bits != 0 ? align_up((size_t)n_tok * sizeof(float), 256) : 0);
 }
 
 tlq_status tlq_apply_best(const void* X, int64_t n_tok, int64_t c_in, int64_t ldx,
@@ -321,17 +383,22 @@ tlq_status tlq_apply_best(const void* X, int64_t n_tok, int64_t c_in, int64_t ld
   float* inv = c.take<float>((size_t)c_in);
   uint16_t* what = c.take<uint16_t>((size_t)c_out * c_in);
   uint32_t* xmax = c.take<uint32_t>(1);
-  uint16_t* xh = bf16 ? c.take<uint16_t>((size_t)n_tok * c_in) : nullptr;
-  if (bf16) TLQ_HIP(launch_xprep(X, n_tok, c_in, ldx, xmax, xh, st));
-  TLQ_HIP(launch_recip(s, c_in, bf16 ? xmax : nullptr, inv, st));
+  const bool act = p->act_bits != 0;
+  if (act && c_in > act_quant_max_cin()) return TLQ_ERR_UNSUPPORTED;
+  uint16_t* xh = (bf16 || act) ? c.take<uint16_t>((size_t)n_tok * c_in) : nullptr;
+  float* sig = act ? c.take<float>((size_t)n_tok) : nullptr;
+  if (bf16 && !act) TLQ_HIP(launch_xprep(X, n_tok, c_in, ldx, xmax, xh, st));
+  TLQ_HIP(launch_recip(s, c_in, (bf16 && !act) ? xmax : nullptr, inv, st));
+  if (act) TLQ_HIP(launch_act_quant(X, n_tok, c_in, ldx, bf16, inv, 0, 1, p->act_bits, xh, sig, st));
   QuantArgs q{};
   q.W = W; q.c_out = c_out; q.c_in = c_in; q.ldw = ldw; q.bf16 = bf16;
   q.bits = p->bits; q.group = p->group; q.symmetric = p->symmetric;
-  q.s_table = s; q.inv_table = inv; q.n_cand = 1; q.what = what; q.what_cand_stride = 0;
+  q.s_table = s; q.inv_table = act ? nullptr : inv; q.n_cand = 1; q.what = what; q.what_cand_stride = 0;
   q.what_f16 = true;
   TLQ_HIP(launch_fake_quant(q, st));
   GemmArgs g{};
-  g.X = bf16 ? (const void*)xh : X; g.n_tok = n_tok; g.c_in = c_in; g.ldx = bf16 ? c_in : ldx;
+  g.X = xh ? (const void*)xh : X; g.n_tok = n_tok; g.c_in = c_in; g.ldx = xh ? c_in : ldx;
+  g.tok_scale = sig;
   g.Wh = what; g.c_out = c_out; g.ldw = c_in; g.w_cand_stride = 0; g.n_cand = 1; g.bf16 = false;
   g.Yout = X_next; g.ldo = ld_next; g.yout_dtype = p->x_dtype;
   return hip_status(launch_gemm_store(g, st));

@@ -50,7 +50,8 @@ constexpr int ROWB = BK * 2;  // bytes per LDS row
 constexpr int PATCH_O = 4, PATCH_T = 8;  // tiles per L2 patch (one patch per XCD at a time)
 
 struct GemmDev {
-  const uint16_t* X; int64_t n_tok, c_in, ldx;
+  const uint16_t* X; int64_t n_tok, c_in, ldx, x_cand_stride;
+  const float* tok_scale;  // [n_cand, n_tok] per-token factor on the accumulators, or NULL
   const uint16_t* Wh; int64_t c_out, ldw, w_cand_stride; int n_cand;
   const void* Yref; int64_t ldy; int ydt; const float* token_w;
   float* partial; float* tok_partial;
@@ -106,8 +107,8 @@ __device__ __forceinline__ void store_y1(void* Y, int odt, int64_t idx, float y)
 // fragment column j; part = sum_j token_w * sq[j].  YDT >= 0 fixes the Y_ref type at
 // compile time; FULL promises that the whole wave tile lies inside the matrix.
 template <int YDT, bool FULL, int FA, int FB>
-__device__ __forceinline__ void loss_rows(const GemmDev& a, f32x16 (&acc)[FA][FB], int64_t ow, int64_t tw,
-                                          float (&sq)[FB], float& part) {
+__device__ __forceinline__ void loss_rows(const GemmDev& a, f32x16 (&acc)[FA][FB], const float* tsc,
+                                          int64_t ow, int64_t tw, float (&sq)[FB], float& part) {
   const int lane = threadIdx.x & 63, frow = lane & 31, fhi = lane >> 5;
   const int ydt = YDT >= 0 ? YDT : a.ydt;
 #pragma unroll
@@ -115,6 +116,8 @@ __device__ __forceinline__ void loss_rows(const GemmDev& a, f32x16 (&acc)[FA][FB
     const int64_t t = tw + j * 32 + frow;
     float sumsq = 0.0f;
     if (FULL || t < a.n_tok) {
+      // residual = y - sg * acc as one fused multiply-add; sg = 1 gives y - acc exactly
+      const float nsg = tsc ? -tsc[t] : -1.0f;
 #pragma unroll
       for (int i = 0; i < FA; ++i)
 #pragma unroll
@@ -125,13 +128,13 @@ __device__ __forceinline__ void loss_rows(const GemmDev& a, f32x16 (&acc)[FA][FB
             load_y4(a.Yref, ydt, t * a.ldy + o, y);
 #pragma unroll
             for (int r = 0; r < 4; ++r) {
-              const float d = y[r] - acc[i][j][q * 4 + r];
+              const float d = __builtin_fmaf(nsg, acc[i][j][q * 4 + r], y[r]);
               sumsq += d * d;
             }
           } else {
             for (int r = 0; r < 4; ++r)
               if (o + r < a.c_out) {
-                const float d = load_y(a.Yref, ydt, t * a.ldy + o + r) - acc[i][j][q * 4 + r];
+                const float d = __builtin_fmaf(nsg, acc[i][j][q * 4 + r], load_y(a.Yref, ydt, t * a.ldy + o + r));
                 sumsq += d * d;
               }
           }
@@ -156,17 +159,20 @@ __device__ __forceinline__ void tile_epilogue(const GemmDev& a, f32x16 (&acc)[FA
   constexpr int WO = FA * 32, WT = FB * 32, NW = NWO * NWT, NT = NW * 64;
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int frow = lane & 31, fhi = lane >> 5;
+  const float* tsc = a.tok_scale ? a.tok_scale + (int64_t)cand * a.n_tok : nullptr;
   if (EPI == EPI_STORE) {
 #pragma unroll
     for (int j = 0; j < FB; ++j) {
       const int64_t t = t0 + wt * WT + j * 32 + frow;
       if (t >= a.n_tok) continue;
+      const float sg = tsc ? tsc[t] : 1.0f;
 #pragma unroll
       for (int i = 0; i < FA; ++i)
 #pragma unroll
         for (int q = 0; q < 4; ++q) {
           const int64_t o = o0 + wo * WO + i * 32 + q * 8 + fhi * 4;
-          float y[4] = {acc[i][j][q * 4], acc[i][j][q * 4 + 1], acc[i][j][q * 4 + 2], acc[i][j][q * 4 + 3]};
+          float y[4] = {sg * acc[i][j][q * 4], sg * acc[i][j][q * 4 + 1], sg * acc[i][j][q * 4 + 2],
+                        sg * acc[i][j][q * 4 + 3]};
           if (o + 3 < a.c_out) store_y4(a.Yout, a.odt, t * a.ldo + o, y);
           else
             for (int r = 0; r < 4; ++r)
@@ -180,10 +186,10 @@ __device__ __forceinline__ void tile_epilogue(const GemmDev& a, f32x16 (&acc)[FA
   float part = 0.0f;
   float sq[FB];
   const bool interior = (o0 + NWO * WO <= a.c_out) && (t0 + BT <= a.n_tok);
-  if (interior && a.ydt == TLQ_F16) loss_rows<TLQ_F16, true, FA, FB>(a, acc, o0 + wo * WO, t0 + wt * WT, sq, part);
-  else if (interior && a.ydt == TLQ_F32) loss_rows<TLQ_F32, true, FA, FB>(a, acc, o0 + wo * WO, t0 + wt * WT, sq, part);
-  else if (interior) loss_rows<TLQ_BF16, true, FA, FB>(a, acc, o0 + wo * WO, t0 + wt * WT, sq, part);
-  else loss_rows<-1, false, FA, FB>(a, acc, o0 + wo * WO, t0 + wt * WT, sq, part);
+  if (interior && a.ydt == TLQ_F16) loss_rows<TLQ_F16, true, FA, FB>(a, acc, tsc, o0 + wo * WO, t0 + wt * WT, sq, part);
+  else if (interior && a.ydt == TLQ_F32) loss_rows<TLQ_F32, true, FA, FB>(a, acc, tsc, o0 + wo * WO, t0 + wt * WT, sq, part);
+  else if (interior) loss_rows<TLQ_BF16, true, FA, FB>(a, acc, tsc, o0 + wo * WO, t0 + wt * WT, sq, part);
+  else loss_rows<-1, false, FA, FB>(a, acc, tsc, o0 + wo * WO, t0 + wt * WT, sq, part);
   if (EPI == EPI_LOSS_TOK) {
 #pragma unroll
     for (int j = 0; j < FB; ++j) {
@@ -259,7 +265,7 @@ __global__ __launch_bounds__((BO / WO) * (BT / WT) * 64) void gemm_kernel(GemmDe
   for (int i = 0; i < CH_B; ++i) {
     const int r = (i * NT + tid) >> 3;
     okb[i] = (t0 + r) < a.n_tok;
-    pb[i] = a.X + (okb[i] ? (t0 + r) : 0) * a.ldx + lchunk * 8;
+    pb[i] = a.X + (int64_t)cand * a.x_cand_stride + (okb[i] ? (t0 + r) : 0) * a.ldx + lchunk * 8;
     lb[i] = BO * ROWB + r * ROWB + (swz(r, lchunk) << 4);
   }
   uint4 ga[CH_A], gb[CH_B];
@@ -429,7 +435,7 @@ __global__ __launch_bounds__(NWO * NWT * 64) void gemm_dma_kernel(GemmDev a) {
   const int64_t vro = (a.c_out - o0) < BO ? (a.c_out - o0) : BO;
   const int64_t vrt = (a.n_tok - t0) < BT ? (a.n_tok - t0) : BT;
   const uint16_t* pA = a.Wh + (int64_t)cand * a.w_cand_stride + o0 * a.ldw;
-  const uint16_t* pB = a.X + t0 * a.ldx;
+  const uint16_t* pB = a.X + (int64_t)cand * a.x_cand_stride + t0 * a.ldx;
   const __amdgpu_buffer_rsrc_t rA = __builtin_amdgcn_make_buffer_rsrc(
       (void*)pA, 0, (int)(((vro - 1) * a.ldw + a.c_in) * 2), 0x00020000);
   const __amdgpu_buffer_rsrc_t rB = __builtin_amdgcn_make_buffer_rsrc(
@@ -598,6 +604,7 @@ void gemm_tile_counts(int64_t n_tok, int64_t c_out, int64_t* tiles_o, int64_t* t
 static GemmDev make_dev(const GemmArgs& g) {
   GemmDev d;
   d.X = (const uint16_t*)g.X; d.n_tok = g.n_tok; d.c_in = g.c_in; d.ldx = g.ldx;
+  d.x_cand_stride = g.x_cand_stride; d.tok_scale = g.tok_scale;
   d.Wh = (const uint16_t*)g.Wh; d.c_out = g.c_out; d.ldw = g.ldw;
   d.w_cand_stride = g.w_cand_stride; d.n_cand = g.n_cand;
   d.Yref = g.Yref; d.ldy = g.ldy; d.ydt = g.yref_dtype; d.token_w = g.token_w;

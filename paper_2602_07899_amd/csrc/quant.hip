@@ -208,6 +208,97 @@ __global__ __launch_bounds__(256) void quant_any_kernel(QuantDev a) {
   }
 }
 
+// ---------------------------------------------------------------------------
+// Q_a (Sec. 3.2.1 f_q; quantiser of Sec. 2.2 applied per token row):
+//   xt = x * inv ; sigma = max(max_c |xt|, 1e-5) / (2^(n-1) - 1) ;
+//   code = clip(rint(xt / sigma), -2^(n-1), 2^(n-1) - 1).
+// One block per token row; the row stays in registers (CH chunks of 8 per
+// thread) while the candidates are looped over.  Codes are written as fp16
+// integers (exact), so the contraction runs on the same MFMA path and the
+// per-token step is applied to the accumulators in its epilogue.
+template <typename T, int CH>
+__global__ __launch_bounds__(256) void act_quant_kernel(const uint16_t* __restrict__ X, int64_t n_tok,
+                                                        int64_t c_in, int64_t ldx,
+                                                        const float* __restrict__ inv_table, int k0, int nb,
+                                                        float qa, uint16_t* __restrict__ codes,
+                                                        float* __restrict__ sigma) {
+  __shared__ float red[2][4];
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int64_t row = blockIdx.x;
+  const int64_t chunks = c_in / 8;
+  float x[CH][8];
+#pragma unroll
+  for (int i = 0; i < CH; ++i) {
+    const int64_t ch = tid + i * 256;
+    uint4 v = make_uint4(0, 0, 0, 0);
+    if (ch < chunks) v = *reinterpret_cast<const uint4*>(X + row * ldx + ch * 8);
+    const uint32_t u[4] = {v.x, v.y, v.z, v.w};
+#pragma unroll
+    for (int j = 0; j < 8; ++j) x[i][j] = T::to_float((uint16_t)(u[j >> 1] >> ((j & 1) * 16)));
+  }
+  for (int kb = 0; kb < nb; ++kb) {
+    const float* inv = inv_table ? inv_table + (int64_t)(k0 + kb) * c_in : nullptr;
+    float amax = 0.0f;
+#pragma unroll
+    for (int i = 0; i < CH; ++i) {
+      const int64_t ch = tid + i * 256;
+      if (ch < chunks) {
+#pragma unroll
+        for (int j = 0; j < 8; ++j) amax = fmaxf(amax, fabsf(x[i][j] * (inv ? inv[ch * 8 + j] : 1.0f)));
+      }
+    }
+#pragma unroll
+    for (int off = 32; off >= 1; off >>= 1) amax = fmaxf(amax, __shfl_xor(amax, off, 64));
+    if (lane == 0) red[kb & 1][wave] = amax;
+    __syncthreads();
+    amax = fmaxf(fmaxf(red[kb & 1][0], red[kb & 1][1]), fmaxf(red[kb & 1][2], red[kb & 1][3]));
+    const float sg = fmaxf(amax, kRangeFloor) / qa;
+    const float rsg = 1.0f / sg;
+    uint16_t* out = codes + ((int64_t)kb * n_tok + row) * c_in;
+#pragma unroll
+    for (int i = 0; i < CH; ++i) {
+      const int64_t ch = tid + i * 256;
+      if (ch < chunks) {
+        uint32_t o[4] = {0, 0, 0, 0};
+#pragma unroll
+        for (int j = 0; j < 8; ++j) {
+          const float xt = x[i][j] * (inv ? inv[ch * 8 + j] : 1.0f);
+          float q = rint_quotient(xt, sg, rsg);
+          q = fminf(fmaxf(q, -qa - 1.0f), qa);
+          o[j >> 1] |= (uint32_t)F16::from_float(q) << ((j & 1) * 16);
+        }
+        *reinterpret_cast<uint4*>(out + ch * 8) = make_uint4(o[0], o[1], o[2], o[3]);
+      }
+    }
+    if (tid == 0) sigma[(int64_t)kb * n_tok + row] = sg;
+  }
+}
+
+int act_quant_max_cin() { return 256 * 8 * 8; }
+
+hipError_t launch_act_quant(const void* X, int64_t n_tok, int64_t c_in, int64_t ldx, bool bf16,
+                            const float* inv_table, int k0, int nb, int act_bits, void* codes,
+                            float* sigma, hipStream_t stream) {
+  ProfScope ps("act_quant", stream, (double)n_tok * (double)c_in * (2.0 + 2.0 * nb));
+  const float qa = (float)((1 << (act_bits - 1)) - 1);
+  const int64_t per_thread = ceil_div(c_in / 8, 256);
+  const uint16_t* x = (const uint16_t*)X;
+  uint16_t* c = (uint16_t*)codes;
+  const unsigned grid = (unsigned)n_tok;
+#define TLQ_AQ(CH)                                                                                   \
+  do {                                                                                               \
+    if (!bf16) act_quant_kernel<F16, CH><<<grid, 256, 0, stream>>>(x, n_tok, c_in, ldx, inv_table, k0, nb, qa, c, sigma); \
+    else act_quant_kernel<BF16, CH><<<grid, 256, 0, stream>>>(x, n_tok, c_in, ldx, inv_table, k0, nb, qa, c, sigma);      \
+  } while (0)
+  if (per_thread <= 1) TLQ_AQ(1);
+  else if (per_thread <= 2) TLQ_AQ(2);
+  else if (per_thread <= 4) TLQ_AQ(4);
+  else if (per_thread <= 8) TLQ_AQ(8);
+  else return hipErrorInvalidValue;
+#undef TLQ_AQ
+  return hipGetLastError();
+}
+
 hipError_t launch_fake_quant(const QuantArgs& q, hipStream_t stream) {
   QuantDev d;
   d.W = (const uint16_t*)q.W; d.c_out = q.c_out; d.c_in = q.c_in; d.ldw = q.ldw;

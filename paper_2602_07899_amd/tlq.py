@@ -50,6 +50,7 @@ _SIGNATURES = {
     "tlq_x_stat": (C.c_int, [_P, _I64, _I64, _I64, _PP, _P, _P, _SZ, _P]),
     "tlq_scale_table": (C.c_int, [_P, _I64, _P, _I32, _P, _P]),
     "tlq_fake_quant": (C.c_int, [_P, _I64, _I64, _I64, _P, _PP, _P, _P, _P, _P, _I64, _P]),
+    "tlq_act_fake_quant": (C.c_int, [_P, _I64, _I64, _I64, _P, _PP, _P, _P, _P]),
     "tlq_weighted_layer_err_workspace_bytes": (_SZ, [_I64, _I64, _I64, _PP]),
     "tlq_weighted_layer_err": (C.c_int, [_P, _I64, _I64, _I64, _P, _I64, _I64, _P, _P, _I64, _P,
                                          _PP, _P, _P, _P, _SZ, _P]),
@@ -141,6 +142,12 @@ def fake_quant(W, s, p, codes=None, zp=None, delta=None, Wdq=None):
     _check(lib().tlq_fake_quant(_ptr(W), co, ci, _ld(W), _ptr(s), C.byref(p), _ptr(codes), _ptr(zp),
                                 _ptr(delta), _ptr(Wdq), 0 if Wdq is None else _ld(Wdq), _stream()),
            "tlq_fake_quant")
+
+
+def act_fake_quant(X, inv_s, p, codes, sigma):
+    n, c = X.shape
+    _check(lib().tlq_act_fake_quant(_ptr(X), n, c, _ld(X), _ptr(inv_s), C.byref(p), _ptr(codes),
+                                    _ptr(sigma), _stream()), "tlq_act_fake_quant")
 
 
 def weighted_layer_err_workspace_bytes(n_tok, c_in, c_out, p):

@@ -60,7 +60,7 @@ def test_scale_search_rejects_bad_arguments():
     assert _search(p, ldy=516) == tlq.ERR_ALIGN
     assert _search(p, ws=None) == tlq.ERR_WORKSPACE
     assert _search(p, wsb=1024) == tlq.ERR_WORKSPACE
-    for field, bad in [("bits", 1), ("bits", 9), ("group", 100), ("symmetric", 2), ("act_bits", 8),
+    for field, bad in [("bits", 1), ("bits", 9), ("group", 100), ("symmetric", 2), ("act_bits", 1), ("act_bits", 9),
                        ("xstat_kind", 2), ("x_dtype", tlq.F32), ("yref_dtype", 3), ("struct_size", 28)]:
         q = tlq.params()
         setattr(q, field, bad)
