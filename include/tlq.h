@@ -37,7 +37,7 @@
  *     xt = x * float(1/s); sigma_t = max(max_c |xt|, 1e-5) / (2^(n-1)-1);
  *     code = clip(rint(xt/sigma_t), -2^(n-1), 2^(n-1)-1); f_q = sigma_t * code . deq^T.
  *     float arithmetic, round half to even.  Applies to tlq_scale_search,
- *     tlq_weighted_layer_err and tlq_apply_best; needs c_in <= 16384.
+ *     tlq_weighted_layer_err and tlq_apply_best.
  *   - x_dtype = BF16: inputs and 16-bit outputs are bf16.  Operands the library
  *     computes itself (the folded weights deq/s) are kept in fp16, and the tokens
  *     are re-expressed in fp16 in the workspace (exact for bf16 values after a

@@ -70,7 +70,7 @@ int act_batch(int64_t n_tok, int64_t c_in, int n_alpha) {
 }
 struct SearchPlan {
   double* xs_partial; float* x_stat; float* s_table; float* inv_table; float* partial;
-  uint16_t* what; uint32_t* xmax; uint16_t* xh; float* sig; uint16_t* xc; int nb; size_t bytes;
+  uint16_t* what; uint32_t* xmax; uint16_t* xh; float* sig; float* rsig; uint16_t* xc; int nb; size_t bytes;
   int64_t tiles_o, tiles_t;
 };
 SearchPlan plan_search(void* ws, int64_t n_tok, int64_t c_in, int64_t c_out, int n_alpha, bool bf16,
@@ -88,6 +88,7 @@ SearchPlan plan_search(void* ws, int64_t n_tok, int64_t c_in, int64_t c_out, int
   s.xh = (bf16 && !act) ? c.take<uint16_t>((size_t)n_tok * c_in) : nullptr;
   s.nb = act ? act_batch(n_tok, c_in, n_alpha) : 0;
   s.sig = act ? c.take<float>((size_t)n_alpha * n_tok) : nullptr;
+  s.rsig = act ? c.take<float>((size_t)s.nb * n_tok) : nullptr;
   s.xc = act ? c.take<uint16_t>((size_t)s.nb * n_tok * c_in) : nullptr;
   s.bytes = c.off;
   return s;
@@ -187,10 +188,9 @@ tlq_status tlq_act_fake_quant(const void* X, int64_t n_tok, int64_t c_in, int64_
   TLQ_TRY(check_params(p));
   if (p->act_bits == 0) return TLQ_ERR_UNSUPPORTED;
   if (!dims_ok(n_tok, c_in, ldx) || (c_in % 8) != 0) return TLQ_ERR_SHAPE;
-  if (c_in > act_quant_max_cin()) return TLQ_ERR_UNSUPPORTED;
   if (!mat16_aligned(X, ldx) || !aligned(codes, 16) || (inv_s && !aligned(inv_s, 4))) return TLQ_ERR_ALIGN;
   return hip_status(launch_act_quant(X, n_tok, c_in, ldx, p->x_dtype == TLQ_BF16, inv_s, 0, 1,
-                                     p->act_bits, codes, sigma, (hipStream_t)stream));
+                                     p->act_bits, codes, sigma, nullptr, (hipStream_t)stream));
 }
 
 // -------------------------------------------------------------------- S3 + S4
@@ -218,14 +218,13 @@ tlq_status tlq_weighted_layer_err(const void* X, int64_t n_tok, int64_t c_in, in
   hipStream_t st = (hipStream_t)stream;
   const bool bf16 = p->x_dtype == TLQ_BF16;
   const bool act = p->act_bits != 0;
-  if (act && c_in > act_quant_max_cin()) return TLQ_ERR_UNSUPPORTED;
   ErrPlan e = plan_err(workspace, n_tok, c_in, c_out, bf16, act);
   GemmArgs g{};
   g.X = X; g.n_tok = n_tok; g.c_in = c_in; g.ldx = ldx;
   g.Wh = Wdq; g.c_out = c_out; g.ldw = ldw; g.w_cand_stride = 0; g.n_cand = 1; g.bf16 = bf16;
   if (act) {
     // Q_a(x * inv_s) as exact fp16 integer codes + per-token steps; the weights stay unfolded
-    TLQ_HIP(launch_act_quant(X, n_tok, c_in, ldx, bf16, inv_s, 0, 1, p->act_bits, e.xh, e.sig, st));
+    TLQ_HIP(launch_act_quant(X, n_tok, c_in, ldx, bf16, inv_s, 0, 1, p->act_bits, e.xh, e.sig, nullptr, st));
     g.X = e.xh; g.ldx = c_in; g.tok_scale = e.sig; g.bf16 = false;
     if (bf16) {
       TLQ_HIP(launch_fold_scale(Wdq, c_out, c_in, ldw, true, nullptr, nullptr, true, e.folded, st));
@@ -281,7 +280,6 @@ tlq_status tlq_scale_search(const void* X, int64_t n_tok, int64_t c_in, int64_t 
   hipStream_t st = (hipStream_t)stream;
   const bool bf16 = p->x_dtype == TLQ_BF16;
   const bool act = p->act_bits != 0;
-  if (act && c_in > act_quant_max_cin()) return TLQ_ERR_UNSUPPORTED;
   SearchPlan s = plan_search(workspace, n_tok, c_in, c_out, n_alpha, bf16, act);
 
   const float* x_stat = x_stat_in;
@@ -320,7 +318,7 @@ tlq_status tlq_scale_search(const void* X, int64_t n_tok, int64_t c_in, int64_t 
     for (int k0 = 0; k0 < n_alpha; k0 += s.nb) {
       const int nb = (n_alpha - k0) < s.nb ? (n_alpha - k0) : s.nb;
       TLQ_HIP(launch_act_quant(X, n_tok, c_in, ldx, bf16, s.inv_table, k0, nb, p->act_bits, s.xc,
-                               s.sig + (size_t)k0 * n_tok, st));
+                               s.sig + (size_t)k0 * n_tok, s.rsig, st));
       GemmArgs b = g;
       b.X = s.xc; b.ldx = c_in; b.x_cand_stride = n_tok * c_in;
       b.tok_scale = s.sig + (size_t)k0 * n_tok;
@@ -384,12 +382,11 @@ tlq_status tlq_apply_best(const void* X, int64_t n_tok, int64_t c_in, int64_t ld
   uint16_t* what = c.take<uint16_t>((size_t)c_out * c_in);
   uint32_t* xmax = c.take<uint32_t>(1);
   const bool act = p->act_bits != 0;
-  if (act && c_in > act_quant_max_cin()) return TLQ_ERR_UNSUPPORTED;
   uint16_t* xh = (bf16 || act) ? c.take<uint16_t>((size_t)n_tok * c_in) : nullptr;
   float* sig = act ? c.take<float>((size_t)n_tok) : nullptr;
   if (bf16 && !act) TLQ_HIP(launch_xprep(X, n_tok, c_in, ldx, xmax, xh, st));
   TLQ_HIP(launch_recip(s, c_in, (bf16 && !act) ? xmax : nullptr, inv, st));
-  if (act) TLQ_HIP(launch_act_quant(X, n_tok, c_in, ldx, bf16, inv, 0, 1, p->act_bits, xh, sig, st));
+  if (act) TLQ_HIP(launch_act_quant(X, n_tok, c_in, ldx, bf16, inv, 0, 1, p->act_bits, xh, sig, nullptr, st));
   QuantArgs q{};
   q.W = W; q.c_out = c_out; q.c_in = c_in; q.ldw = ldw; q.bf16 = bf16;
   q.bits = p->bits; q.group = p->group; q.symmetric = p->symmetric;

@@ -91,11 +91,11 @@ hipError_t launch_fake_quant(const QuantArgs& a, hipStream_t stream);
 
 // Q_a: per-token symmetric activation fake-quant of X * diag(inv_k) for candidates k0 .. k0+nb-1.
 // inv_table: [.., c_in] rows (row k used for candidate k) or NULL (ones).
-// codes: fp16 integers [nb, n_tok, c_in]; sigma: float [nb, n_tok] (already offset to k0).
-int act_quant_max_cin();
+// codes: fp16 integers [nb, n_tok, c_in]; sigma: float [nb, n_tok] (already offset to k0);
+// rsigma: optional scratch of the same shape for the reciprocal steps.
 hipError_t launch_act_quant(const void* X, int64_t n_tok, int64_t c_in, int64_t ldx, bool bf16,
                             const float* inv_table, int k0, int nb, int act_bits, void* codes,
-                            float* sigma, hipStream_t stream);
+                            float* sigma, float* rsigma, hipStream_t stream);
 
 // Wout[o,c] = round16(Win[o,c] * inv_s[c])
 hipError_t launch_fold_scale(const void* Win, int64_t c_out, int64_t c_in, int64_t ldw, bool bf16,

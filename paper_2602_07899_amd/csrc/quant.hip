@@ -212,90 +212,125 @@ __global__ __launch_bounds__(256) void quant_any_kernel(QuantDev a) {
 // Q_a (Sec. 3.2.1 f_q; quantiser of Sec. 2.2 applied per token row):
 //   xt = x * inv ; sigma = max(max_c |xt|, 1e-5) / (2^(n-1) - 1) ;
 //   code = clip(rint(xt / sigma), -2^(n-1), 2^(n-1) - 1).
-// One block per token row; the row stays in registers (CH chunks of 8 per
-// thread) while the candidates are looped over.  Codes are written as fp16
-// integers (exact), so the contraction runs on the same MFMA path and the
-// per-token step is applied to the accumulators in its epilogue.
-template <typename T, int CH>
-__global__ __launch_bounds__(256) void act_quant_kernel(const uint16_t* __restrict__ X, int64_t n_tok,
-                                                        int64_t c_in, int64_t ldx,
-                                                        const float* __restrict__ inv_table, int k0, int nb,
-                                                        float qa, uint16_t* __restrict__ codes,
-                                                        float* __restrict__ sigma) {
-  __shared__ float red[2][4];
-  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-  const int64_t row = blockIdx.x;
-  const int64_t chunks = c_in / 8;
-  float x[CH][8];
+// Two tiled passes so that a tile of X (8 rows x 8 channels per lane) stays in
+// registers for all candidates and a candidate's reciprocal scales are loaded
+// once per 8 rows: (1) row maxima, combined across the channel strips with an
+// integer atomic max on the float bit pattern (non-negative floats order like
+// integers, so the result is exact and order independent); (2) the codes,
+// written as fp16 integers (exact), so the contraction runs on the same MFMA
+// path and the per-token step is applied to the accumulators in its epilogue.
+constexpr int kAqRows = 8;      // rows per wave
+constexpr int kAqCols = 512;    // channels per block strip (64 lanes x 8)
+
+template <typename T>
+__device__ __forceinline__ void aq_load_tile(const uint16_t* __restrict__ X, int64_t n_tok, int64_t c_in,
+                                             int64_t ldx, int64_t r0, int64_t c, float (&x)[kAqRows][8]) {
 #pragma unroll
-  for (int i = 0; i < CH; ++i) {
-    const int64_t ch = tid + i * 256;
+  for (int r = 0; r < kAqRows; ++r) {
     uint4 v = make_uint4(0, 0, 0, 0);
-    if (ch < chunks) v = *reinterpret_cast<const uint4*>(X + row * ldx + ch * 8);
+    if (r0 + r < n_tok && c < c_in) v = *reinterpret_cast<const uint4*>(X + (r0 + r) * ldx + c);
     const uint32_t u[4] = {v.x, v.y, v.z, v.w};
 #pragma unroll
-    for (int j = 0; j < 8; ++j) x[i][j] = T::to_float((uint16_t)(u[j >> 1] >> ((j & 1) * 16)));
+    for (int j = 0; j < 8; ++j) x[r][j] = T::to_float((uint16_t)(u[j >> 1] >> ((j & 1) * 16)));
   }
-  for (int kb = 0; kb < nb; ++kb) {
-    const float* inv = inv_table ? inv_table + (int64_t)(k0 + kb) * c_in : nullptr;
-    float amax = 0.0f;
+}
+__device__ __forceinline__ void aq_load_inv(const float* __restrict__ inv, int64_t c, int64_t c_in, float (&iv)[8]) {
 #pragma unroll
-    for (int i = 0; i < CH; ++i) {
-      const int64_t ch = tid + i * 256;
-      if (ch < chunks) {
-#pragma unroll
-        for (int j = 0; j < 8; ++j) amax = fmaxf(amax, fabsf(x[i][j] * (inv ? inv[ch * 8 + j] : 1.0f)));
-      }
-    }
-#pragma unroll
-    for (int off = 32; off >= 1; off >>= 1) amax = fmaxf(amax, __shfl_xor(amax, off, 64));
-    if (lane == 0) red[kb & 1][wave] = amax;
-    __syncthreads();
-    amax = fmaxf(fmaxf(red[kb & 1][0], red[kb & 1][1]), fmaxf(red[kb & 1][2], red[kb & 1][3]));
-    const float sg = fmaxf(amax, kRangeFloor) / qa;
-    const float rsg = 1.0f / sg;
-    uint16_t* out = codes + ((int64_t)kb * n_tok + row) * c_in;
-#pragma unroll
-    for (int i = 0; i < CH; ++i) {
-      const int64_t ch = tid + i * 256;
-      if (ch < chunks) {
-        uint32_t o[4] = {0, 0, 0, 0};
-#pragma unroll
-        for (int j = 0; j < 8; ++j) {
-          const float xt = x[i][j] * (inv ? inv[ch * 8 + j] : 1.0f);
-          float q = rint_quotient(xt, sg, rsg);
-          q = fminf(fmaxf(q, -qa - 1.0f), qa);
-          o[j >> 1] |= (uint32_t)F16::from_float(q) << ((j & 1) * 16);
-        }
-        *reinterpret_cast<uint4*>(out + ch * 8) = make_uint4(o[0], o[1], o[2], o[3]);
-      }
-    }
-    if (tid == 0) sigma[(int64_t)kb * n_tok + row] = sg;
+  for (int j = 0; j < 8; ++j) iv[j] = 1.0f;
+  if (inv && c < c_in) {
+    const float4 a = *reinterpret_cast<const float4*>(inv + c), b = *reinterpret_cast<const float4*>(inv + c + 4);
+    iv[0] = a.x; iv[1] = a.y; iv[2] = a.z; iv[3] = a.w; iv[4] = b.x; iv[5] = b.y; iv[6] = b.z; iv[7] = b.w;
   }
 }
 
-int act_quant_max_cin() { return 256 * 8 * 8; }
+template <typename T>
+__global__ __launch_bounds__(256) void act_amax_kernel(const uint16_t* __restrict__ X, int64_t n_tok,
+                                                       int64_t c_in, int64_t ldx,
+                                                       const float* __restrict__ inv_table, int k0, int nb,
+                                                       uint32_t* __restrict__ amax_bits) {
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int64_t c = (int64_t)blockIdx.x * kAqCols + lane * 8;
+  const int64_t r0 = ((int64_t)blockIdx.y * 4 + wave) * kAqRows;
+  if (r0 >= n_tok) return;
+  float x[kAqRows][8];
+  aq_load_tile<T>(X, n_tok, c_in, ldx, r0, c, x);
+  for (int kb = 0; kb < nb; ++kb) {
+    float iv[8];
+    aq_load_inv(inv_table ? inv_table + (int64_t)(k0 + kb) * c_in : nullptr, c, c_in, iv);
+#pragma unroll
+    for (int r = 0; r < kAqRows; ++r) {
+      float m = 0.0f;
+#pragma unroll
+      for (int j = 0; j < 8; ++j) m = fmaxf(m, fabsf(x[r][j] * iv[j]));
+#pragma unroll
+      for (int off = 32; off >= 1; off >>= 1) m = fmaxf(m, __shfl_xor(m, off, 64));
+      if (lane == 0 && r0 + r < n_tok)
+        atomicMax(amax_bits + (int64_t)kb * n_tok + r0 + r, __builtin_bit_cast(uint32_t, m));
+    }
+  }
+}
+
+// in place: amax bit pattern -> sigma; optional reciprocal table
+__global__ void act_sigma_kernel(float* __restrict__ sig, int64_t n, float qa, float* __restrict__ rsig) {
+  const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  if (i >= n) return;
+  const float sg = fmaxf(sig[i], kRangeFloor) / qa;   // the stored bits are the float maximum
+  sig[i] = sg;
+  if (rsig) rsig[i] = 1.0f / sg;
+}
+
+__global__ void fill_zero_u32_kernel(uint32_t* __restrict__ p, int64_t n) {
+  const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  if (i < n) p[i] = 0u;
+}
+
+template <typename T>
+__global__ __launch_bounds__(256) void act_codes_kernel(const uint16_t* __restrict__ X, int64_t n_tok,
+                                                        int64_t c_in, int64_t ldx,
+                                                        const float* __restrict__ inv_table, int k0, int nb,
+                                                        const float* __restrict__ sig,
+                                                        const float* __restrict__ rsig, float qa,
+                                                        uint16_t* __restrict__ codes) {
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int64_t c = (int64_t)blockIdx.x * kAqCols + lane * 8;
+  const int64_t r0 = ((int64_t)blockIdx.y * 4 + wave) * kAqRows;
+  if (r0 >= n_tok || c >= c_in) return;
+  float x[kAqRows][8];
+  aq_load_tile<T>(X, n_tok, c_in, ldx, r0, c, x);
+  for (int kb = 0; kb < nb; ++kb) {
+    float iv[8];
+    aq_load_inv(inv_table ? inv_table + (int64_t)(k0 + kb) * c_in : nullptr, c, c_in, iv);
+#pragma unroll
+    for (int r = 0; r < kAqRows; ++r) {
+      if (r0 + r >= n_tok) break;
+      const float sg = sig[(int64_t)kb * n_tok + r0 + r];
+      const float rs = rsig ? rsig[(int64_t)kb * n_tok + r0 + r] : 1.0f / sg;
+      uint32_t o[4] = {0, 0, 0, 0};
+#pragma unroll
+      for (int j = 0; j < 8; ++j) {
+        float q = rint_quotient(x[r][j] * iv[j], sg, rs);
+        q = fminf(fmaxf(q, -qa - 1.0f), qa);
+        o[j >> 1] |= (uint32_t)F16::from_float(q) << ((j & 1) * 16);
+      }
+      *reinterpret_cast<uint4*>(codes + ((int64_t)kb * n_tok + r0 + r) * c_in + c) = make_uint4(o[0], o[1], o[2], o[3]);
+    }
+  }
+}
 
 hipError_t launch_act_quant(const void* X, int64_t n_tok, int64_t c_in, int64_t ldx, bool bf16,
                             const float* inv_table, int k0, int nb, int act_bits, void* codes,
-                            float* sigma, hipStream_t stream) {
-  ProfScope ps("act_quant", stream, (double)n_tok * (double)c_in * (2.0 + 2.0 * nb));
+                            float* sigma, float* rsigma, hipStream_t stream) {
+  ProfScope ps("act_quant", stream, (double)n_tok * (double)c_in * (4.0 + 2.0 * nb));
   const float qa = (float)((1 << (act_bits - 1)) - 1);
-  const int64_t per_thread = ceil_div(c_in / 8, 256);
   const uint16_t* x = (const uint16_t*)X;
-  uint16_t* c = (uint16_t*)codes;
-  const unsigned grid = (unsigned)n_tok;
-#define TLQ_AQ(CH)                                                                                   \
-  do {                                                                                               \
-    if (!bf16) act_quant_kernel<F16, CH><<<grid, 256, 0, stream>>>(x, n_tok, c_in, ldx, inv_table, k0, nb, qa, c, sigma); \
-    else act_quant_kernel<BF16, CH><<<grid, 256, 0, stream>>>(x, n_tok, c_in, ldx, inv_table, k0, nb, qa, c, sigma);      \
-  } while (0)
-  if (per_thread <= 1) TLQ_AQ(1);
-  else if (per_thread <= 2) TLQ_AQ(2);
-  else if (per_thread <= 4) TLQ_AQ(4);
-  else if (per_thread <= 8) TLQ_AQ(8);
-  else return hipErrorInvalidValue;
-#undef TLQ_AQ
+  const int64_t n = (int64_t)nb * n_tok;
+  dim3 grid((unsigned)ceil_div(c_in, kAqCols), (unsigned)ceil_div(n_tok, 4 * kAqRows));
+  fill_zero_u32_kernel<<<(unsigned)ceil_div(n, 256), 256, 0, stream>>>((uint32_t*)sigma, n);
+  if (!bf16) act_amax_kernel<F16><<<grid, 256, 0, stream>>>(x, n_tok, c_in, ldx, inv_table, k0, nb, (uint32_t*)sigma);
+  else act_amax_kernel<BF16><<<grid, 256, 0, stream>>>(x, n_tok, c_in, ldx, inv_table, k0, nb, (uint32_t*)sigma);
+  act_sigma_kernel<<<(unsigned)ceil_div(n, 256), 256, 0, stream>>>(sigma, n, qa, rsigma);
+  if (!bf16) act_codes_kernel<F16><<<grid, 256, 0, stream>>>(x, n_tok, c_in, ldx, inv_table, k0, nb, sigma, rsigma, qa, (uint16_t*)codes);
+  else act_codes_kernel<BF16><<<grid, 256, 0, stream>>>(x, n_tok, c_in, ldx, inv_table, k0, nb, sigma, rsigma, qa, (uint16_t*)codes);
   return hipGetLastError();
 }
 
