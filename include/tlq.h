@@ -92,6 +92,25 @@ tlq_status tlq_x_stat(const void* X, int64_t n_tok, int64_t c_in, int64_t ldx,
                       const tlq_params* p, float* x_stat,
                       void* workspace, size_t workspace_bytes, void* stream);
 
+/* ---- gradient-guided token selection (Sec. 3.1.2).  G holds per-sample gradients with
+ * respect to the layer input, sample major: [n_samples * n_pos, c] x_dtype.
+ *   tlq_token_importance: sum_n[n] = sum_b ||g_{b,n}||, n < n_pos (gradient-statistic eq.);
+ *     the norm is mean_c |g| (l2 = 0, the text's description) or the Euclidean norm (l2 = 1);
+ *     double accumulation in a fixed order; sum_n: out double [n_pos].
+ *   tlq_topk_mask: I = Top_k({sum_n}) (selection eq.; the paper keeps k = n_pos/2); ties go
+ *     to the lower position; mask: out uint8 [n_pos], 1 = selected.  n_pos <= 65536.
+ *   tlq_x_stat_masked: x_stat[c] = max over rows t with pos_mask[t mod period] != 0 of
+ *     |X[t,c]| (x_stat eq.; X stacks samples of `period` positions); workspace as tlq_x_stat.
+ * The result feeds tlq_scale_search through x_stat_in. */
+size_t tlq_token_importance_workspace_bytes(int64_t n_samples, int64_t n_pos);
+tlq_status tlq_token_importance(const void* G, int64_t n_samples, int64_t n_pos, int64_t c,
+                                int64_t ldg, int32_t l2, const tlq_params* p, double* sum_n,
+                                void* workspace, size_t workspace_bytes, void* stream);
+tlq_status tlq_topk_mask(const double* sum_n, int64_t n_pos, int64_t k, uint8_t* mask, void* stream);
+tlq_status tlq_x_stat_masked(const void* X, int64_t n_tok, int64_t c_in, int64_t ldx,
+                             const uint8_t* pos_mask, int64_t period, const tlq_params* p,
+                             float* x_stat, void* workspace, size_t workspace_bytes, void* stream);
+
 /* ---- S1: candidate scales (Sec. 3.1.2 scale eq.; Sec. 3.2.1 per-layer form).
  * s_table[k,c] = float( pow( double(max(x_stat[c], 2^-14)), double(alpha[k]) ) ).
  * x_stat: in, float [c_in]; alpha_grid: in, float [n_alpha];

@@ -86,6 +86,38 @@ def x_stat_max(X, token_mask=None):
     return X.max(axis=0).astype(np.float32)
 
 
+def token_importance(G, n_samples, l2=False):
+    """sum_n = sum_b || g_{b,n} ||  (Sec. 3.1.2, gradient-statistic equation).
+    G: [n_samples * N, C] per-sample gradients w.r.t. the layer input, sample
+    major.  The text describes the norm as the absolute values averaged over
+    the channel dimension (l2=False, the reading taken); l2=True uses the
+    Euclidean norm instead.  float64; returns [N]."""
+    G = to_f64(G)
+    n_pos = G.shape[0] // n_samples
+    G = G.reshape(n_samples, n_pos, -1)
+    per = np.sqrt((G * G).sum(axis=2)) if l2 else np.abs(G).mean(axis=2)
+    return per.sum(axis=0)
+
+
+def top_fraction_mask(sum_n, k):
+    """I = Top_k({sum_n})  (Sec. 3.1.2, selection equation; the paper keeps the
+    top 50 %).  Ties go to the lower position.  Returns a bool mask [N]."""
+    sum_n = np.asarray(sum_n)
+    order = np.lexsort((np.arange(sum_n.size), -sum_n))   # by value descending, then index
+    mask = np.zeros(sum_n.size, dtype=bool)
+    mask[order[:k]] = True
+    return mask
+
+
+def x_stat_topk_max(X, pos_mask):
+    """x_stat_c = max_{i in I} |X_{i,c}|  (Sec. 3.1.2, x_stat equation) where I is a set of
+    token positions and X stacks samples of len(pos_mask) tokens each."""
+    X = np.abs(to_f64(X))
+    period = len(pos_mask)
+    rows = np.asarray(pos_mask, bool)[np.arange(X.shape[0]) % period]
+    return X[rows].max(axis=0).astype(np.float32)
+
+
 # --------------------------------------------------------------------------
 # S1  scale table
 # --------------------------------------------------------------------------

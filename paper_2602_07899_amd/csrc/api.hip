@@ -149,6 +149,45 @@ tlq_status tlq_x_stat(const void* X, int64_t n_tok, int64_t c_in, int64_t ldx,
                                  (double*)workspace, x_stat, (hipStream_t)stream));
 }
 
+// ------------------------------------------- gradient-guided selection (Sec. 3.1.2)
+size_t tlq_token_importance_workspace_bytes(int64_t n_samples, int64_t n_pos) {
+  if (n_samples <= 0 || n_pos <= 0) return 0;
+  return align_up((size_t)n_samples * (size_t)n_pos * sizeof(double), 256);
+}
+
+tlq_status tlq_token_importance(const void* G, int64_t n_samples, int64_t n_pos, int64_t c,
+                                int64_t ldg, int32_t l2, const tlq_params* p, double* sum_n,
+                                void* workspace, size_t workspace_bytes, void* stream) {
+  if (!G || !sum_n) return TLQ_ERR_NULL;
+  TLQ_TRY(check_params(p));
+  if (n_samples <= 0 || n_pos <= 0 || c <= 0 || ldg < c || n_samples * n_pos >= (1LL << 31))
+    return TLQ_ERR_SHAPE;
+  if (l2 != 0 && l2 != 1) return TLQ_ERR_UNSUPPORTED;
+  if (!aligned(G, 2) || !aligned(sum_n, 8)) return TLQ_ERR_ALIGN;
+  TLQ_TRY(check_ws(workspace, workspace_bytes, tlq_token_importance_workspace_bytes(n_samples, n_pos)));
+  return hip_status(launch_token_importance(G, n_samples, n_pos, c, ldg, p->x_dtype == TLQ_BF16, l2 != 0,
+                                            (double*)workspace, sum_n, (hipStream_t)stream));
+}
+
+tlq_status tlq_topk_mask(const double* sum_n, int64_t n_pos, int64_t k, uint8_t* mask, void* stream) {
+  if (!sum_n || !mask) return TLQ_ERR_NULL;
+  if (n_pos <= 0 || k < 0 || k > n_pos) return TLQ_ERR_SHAPE;
+  if (n_pos > 65536) return TLQ_ERR_UNSUPPORTED;
+  return hip_status(launch_topk_mask(sum_n, n_pos, k, mask, (hipStream_t)stream));
+}
+
+tlq_status tlq_x_stat_masked(const void* X, int64_t n_tok, int64_t c_in, int64_t ldx,
+                             const uint8_t* pos_mask, int64_t period, const tlq_params* p,
+                             float* x_stat, void* workspace, size_t workspace_bytes, void* stream) {
+  if (!X || !x_stat || !pos_mask) return TLQ_ERR_NULL;
+  TLQ_TRY(check_params(p));
+  if (!dims_ok(n_tok, c_in, ldx) || (c_in % 8) != 0 || period <= 0 || period > n_tok) return TLQ_ERR_SHAPE;
+  if (!mat16_aligned(X, ldx)) return TLQ_ERR_ALIGN;
+  TLQ_TRY(check_ws(workspace, workspace_bytes, tlq_x_stat_workspace_bytes(n_tok, c_in)));
+  return hip_status(launch_xstat(X, n_tok, c_in, ldx, p->x_dtype == TLQ_BF16, 1, (double*)workspace,
+                                 x_stat, (hipStream_t)stream, pos_mask, period));
+}
+
 // ------------------------------------------------------------------------ S1
 tlq_status tlq_scale_table(const float* x_stat, int64_t c_in, const float* alpha_grid,
                            int32_t n_alpha, float* s_table, void* stream) {

@@ -49,8 +49,14 @@ struct ProfScope {
 // ---- kernel launchers (each enqueues on `stream`, returns hipGetLastError) --
 // S0: column mean/max of |X|; partial: double [n_chunks, c_in]
 int xstat_chunks(int64_t n_tok);
+// pos_mask (optional): only rows r with pos_mask[r % period] != 0 take part
 hipError_t launch_xstat(const void* X, int64_t n_tok, int64_t c_in, int64_t ldx, bool bf16,
-                        int kind, double* partial, float* x_stat, hipStream_t stream);
+                        int kind, double* partial, float* x_stat, hipStream_t stream,
+                        const uint8_t* pos_mask = nullptr, int64_t period = 1);
+// gradient-guided token selection (select.hip)
+hipError_t launch_token_importance(const void* G, int64_t n_samples, int64_t n_pos, int64_t c, int64_t ldg,
+                                   bool bf16, bool l2, double* row_norm, double* sum_n, hipStream_t stream);
+hipError_t launch_topk_mask(const double* sum_n, int64_t n_pos, int64_t k, uint8_t* mask, hipStream_t stream);
 // S1
 // inv_table (optional) = 2^shift / s, where shift comes from `xmax_bits` (see launch_xprep) or is 0
 hipError_t launch_scale_table(const float* x_stat, int64_t c_in, const float* alpha, int n_alpha,

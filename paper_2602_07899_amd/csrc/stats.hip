@@ -23,7 +23,7 @@ int xstat_chunks(int64_t n_tok) {
 template <typename T, int KIND>
 __global__ __launch_bounds__(kXsThreads) void xstat_partial_kernel(
     const uint16_t* __restrict__ X, int64_t n_tok, int64_t c_in, int64_t ldx, int rows_per_chunk,
-    double* __restrict__ partial) {
+    double* __restrict__ partial, const uint8_t* __restrict__ pos_mask, int64_t period) {
   __shared__ double red[4][kXsCols];
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   const int64_t c0 = (int64_t)blockIdx.x * kXsCols + lane * 8;
@@ -35,6 +35,7 @@ __global__ __launch_bounds__(kXsThreads) void xstat_partial_kernel(
   for (int j = 0; j < 8; ++j) acc[j] = 0.0;
   if (c0 < c_in) {
     for (int64_t r = r0 + wave; r < r1; r += 4) {
+      if (pos_mask && !pos_mask[r % period]) continue;   // token position not in the selected set
       const uint4 v = *reinterpret_cast<const uint4*>(X + r * ldx + c0);
       const uint32_t w[4] = {v.x, v.y, v.z, v.w};
 #pragma unroll
@@ -73,17 +74,18 @@ __global__ void xstat_final_kernel(const double* __restrict__ partial, int n_chu
 }
 
 hipError_t launch_xstat(const void* X, int64_t n_tok, int64_t c_in, int64_t ldx, bool bf16,
-                        int kind, double* partial, float* x_stat, hipStream_t stream) {
+                        int kind, double* partial, float* x_stat, hipStream_t stream,
+                        const uint8_t* pos_mask, int64_t period) {
   const int chunks = xstat_chunks(n_tok);
   const int rows = (int)ceil_div(n_tok, chunks);
   dim3 grid((unsigned)ceil_div(c_in, kXsCols), (unsigned)chunks);
   const uint16_t* x = (const uint16_t*)X;
   {
     ProfScope ps("xstat_partial", stream, 2.0 * (double)n_tok * (double)c_in);
-    if (!bf16 && kind == 0) xstat_partial_kernel<F16, 0><<<grid, kXsThreads, 0, stream>>>(x, n_tok, c_in, ldx, rows, partial);
-    else if (!bf16) xstat_partial_kernel<F16, 1><<<grid, kXsThreads, 0, stream>>>(x, n_tok, c_in, ldx, rows, partial);
-    else if (kind == 0) xstat_partial_kernel<BF16, 0><<<grid, kXsThreads, 0, stream>>>(x, n_tok, c_in, ldx, rows, partial);
-    else xstat_partial_kernel<BF16, 1><<<grid, kXsThreads, 0, stream>>>(x, n_tok, c_in, ldx, rows, partial);
+    if (!bf16 && kind == 0) xstat_partial_kernel<F16, 0><<<grid, kXsThreads, 0, stream>>>(x, n_tok, c_in, ldx, rows, partial, pos_mask, period);
+    else if (!bf16) xstat_partial_kernel<F16, 1><<<grid, kXsThreads, 0, stream>>>(x, n_tok, c_in, ldx, rows, partial, pos_mask, period);
+    else if (kind == 0) xstat_partial_kernel<BF16, 0><<<grid, kXsThreads, 0, stream>>>(x, n_tok, c_in, ldx, rows, partial, pos_mask, period);
+    else xstat_partial_kernel<BF16, 1><<<grid, kXsThreads, 0, stream>>>(x, n_tok, c_in, ldx, rows, partial, pos_mask, period);
   }
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) return e;

@@ -48,6 +48,10 @@ _SIGNATURES = {
     "tlq_version": (C.c_int, []),
     "tlq_x_stat_workspace_bytes": (_SZ, [_I64, _I64]),
     "tlq_x_stat": (C.c_int, [_P, _I64, _I64, _I64, _PP, _P, _P, _SZ, _P]),
+    "tlq_token_importance_workspace_bytes": (_SZ, [_I64, _I64]),
+    "tlq_token_importance": (C.c_int, [_P, _I64, _I64, _I64, _I64, _I32, _PP, _P, _P, _SZ, _P]),
+    "tlq_topk_mask": (C.c_int, [_P, _I64, _I64, _P, _P]),
+    "tlq_x_stat_masked": (C.c_int, [_P, _I64, _I64, _I64, _P, _I64, _PP, _P, _P, _SZ, _P]),
     "tlq_scale_table": (C.c_int, [_P, _I64, _P, _I32, _P, _P]),
     "tlq_fake_quant": (C.c_int, [_P, _I64, _I64, _I64, _P, _PP, _P, _P, _P, _P, _I64, _P]),
     "tlq_act_fake_quant": (C.c_int, [_P, _I64, _I64, _I64, _P, _PP, _P, _P, _P]),
@@ -128,6 +132,28 @@ def x_stat(X, p, out, workspace=None):
     ws = workspace if workspace is not None else _ws(x_stat_workspace_bytes(n, c), X)
     _check(lib().tlq_x_stat(_ptr(X), n, c, _ld(X), C.byref(p), _ptr(out), _ptr(ws), ws.numel(),
                             _stream()), "tlq_x_stat")
+    return out
+
+
+def token_importance(G, n_samples, p, sum_n, l2=False, workspace=None):
+    rows, c = G.shape
+    n_pos = rows // n_samples
+    ws = workspace if workspace is not None else _ws(lib().tlq_token_importance_workspace_bytes(n_samples, n_pos), G)
+    _check(lib().tlq_token_importance(_ptr(G), n_samples, n_pos, c, _ld(G), 1 if l2 else 0, C.byref(p),
+                                      _ptr(sum_n), _ptr(ws), ws.numel(), _stream()), "tlq_token_importance")
+    return sum_n
+
+
+def topk_mask(sum_n, k, mask):
+    _check(lib().tlq_topk_mask(_ptr(sum_n), sum_n.numel(), k, _ptr(mask), _stream()), "tlq_topk_mask")
+    return mask
+
+
+def x_stat_masked(X, pos_mask, p, out, workspace=None):
+    n, c = X.shape
+    ws = workspace if workspace is not None else _ws(x_stat_workspace_bytes(n, c), X)
+    _check(lib().tlq_x_stat_masked(_ptr(X), n, c, _ld(X), _ptr(pos_mask), pos_mask.numel(), C.byref(p),
+                                   _ptr(out), _ptr(ws), ws.numel(), _stream()), "tlq_x_stat_masked")
     return out
 
 

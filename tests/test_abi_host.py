@@ -91,6 +91,13 @@ def test_other_entry_points_reject_bad_arguments():
     assert l.tlq_apply_best(FAKE, 4, 128, 128, FAKE, 4, 128, FAKE, bp, FAKE, 8, FAKE, 8,
                             None) == tlq.ERR_WORKSPACE
     assert l.tlq_profile_get(99, None, 0, None, None, None) == tlq.ERR_SHAPE
+    assert l.tlq_token_importance(None, 2, 4, 8, 8, 0, bp, FAKE, FAKE, 1 << 20, None) == tlq.ERR_NULL
+    assert l.tlq_token_importance(FAKE, 2, 4, 8, 4, 0, bp, FAKE, FAKE, 1 << 20, None) == tlq.ERR_SHAPE
+    assert l.tlq_token_importance(FAKE, 2, 4, 8, 8, 0, bp, FAKE, None, 0, None) == tlq.ERR_WORKSPACE
+    assert l.tlq_topk_mask(FAKE, 4, 5, FAKE, None) == tlq.ERR_SHAPE
+    assert l.tlq_topk_mask(FAKE, 1 << 20, 5, FAKE, None) == tlq.ERR_UNSUPPORTED
+    assert l.tlq_x_stat_masked(FAKE, 4, 8, 8, None, 2, bp, FAKE, FAKE, 1 << 20, None) == tlq.ERR_NULL
+    assert l.tlq_x_stat_masked(FAKE, 4, 8, 8, FAKE, 0, bp, FAKE, FAKE, 1 << 20, None) == tlq.ERR_SHAPE
     assert l.tlq_rmsnorm_mul(None, 4, 8, 8, None, 0, None, None, 0, 0, bp, FAKE, 8, None) == tlq.ERR_NULL
     assert l.tlq_rmsnorm_mul(FAKE, 4, 8, 8, None, 0, None, None, 0, 0, bp, FAKE, 4, None) == tlq.ERR_SHAPE
     assert l.tlq_rmsnorm_mul(FAKE, 4, 8, 8, None, 0, None, None, 4, 2, bp, FAKE, 8, None) == tlq.ERR_SHAPE

@@ -393,3 +393,29 @@ def test_act_quant_limits():
     Xi[:, 0] = 127
     codes, sigma = orc.act_quant(Xi, None, 8)
     assert np.all(sigma == 1.0) and np.array_equal(codes, Xi.astype(np.int16))
+
+
+# ------------------------------------------- gradient-guided token selection
+def test_token_importance_and_topk_selection():
+    rng = np.random.default_rng(4)
+    B, N, C = 3, 10, 6
+    G = rng.standard_normal((B * N, C)).astype(np.float32)
+    s1 = orc.token_importance(G, B)
+    s2 = orc.token_importance(G, B, l2=True)
+    for n in range(N):                                  # written out from the definition
+        a = sum(sum(abs(float(G[b * N + n, c])) for c in range(C)) / C for b in range(B))
+        e = sum(sum(float(G[b * N + n, c]) ** 2 for c in range(C)) ** 0.5 for b in range(B))
+        assert abs(s1[n] - a) < 1e-12 and abs(s2[n] - e) < 1e-12
+    m = orc.top_fraction_mask(s1, N // 2)
+    assert m.sum() == N // 2 and s1[m].min() >= s1[~m].max()
+    assert orc.top_fraction_mask(np.array([1.0, 3.0, 3.0, 0.5]), 2).tolist() == [False, True, True, False]
+    assert orc.top_fraction_mask(np.array([2.0, 2.0, 2.0, 2.0]), 2).tolist() == [True, True, False, False]
+    # masked channel maximum over the selected positions of every sample
+    X = rng.standard_normal((B * N, C)).astype(np.float16)
+    xs = orc.x_stat_topk_max(X, m)
+    ref = np.zeros(C)
+    for r in range(B * N):
+        if m[r % N]:
+            ref = np.maximum(ref, np.abs(X[r].astype(np.float64)))
+    assert np.array_equal(xs, ref.astype(np.float32))
+    assert np.array_equal(orc.x_stat_topk_max(X, np.ones(N, bool)), orc.x_stat_max(X))
