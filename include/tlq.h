@@ -205,6 +205,30 @@ tlq_status tlq_rmsnorm_mul(const void* Z, int64_t n_tok, int64_t c, int64_t ldz,
                            int32_t split, const tlq_params* p, void* X_out, int64_t ld_out,
                            void* stream);
 
+/* ---- decoder-block glue for sequential calibration of a stack (Sec. 3.2.1:
+ * activations are propagated through the model between two searches; the block
+ * itself is the workload's, not the paper's).  All matrices are 16-bit
+ * (p->x_dtype) device pointers, 16-byte aligned, row strides in elements and
+ * multiples of 8; nothing is allocated; work is enqueued on `stream`.
+ *
+ * tlq_causal_attention: Out[t, h*128 .. h*128+127] =
+ *   sum_{j <= t, same sample} softmax_j(q_t . k_j / sqrt(128)) v_j  per head h.
+ * Rows are grouped in consecutive blocks of seq_len (one calibration sample
+ * each); n_tok must be a multiple of seq_len.  head_dim must be 128
+ * (TLQ_ERR_UNSUPPORTED otherwise).  Q, K, V may be column slices of one matrix.
+ * Scores and the softmax are float; probabilities are rounded to x_dtype before
+ * the second product; Out is rounded to x_dtype. */
+tlq_status tlq_causal_attention(const void* Q, int64_t ldq, const void* K, int64_t ldk, const void* V,
+                                int64_t ldv, int64_t n_tok, int32_t n_heads, int32_t head_dim,
+                                int32_t seq_len, const tlq_params* p, void* Out, int64_t ldo,
+                                void* stream);
+/* Out = G / (1 + exp(-G)) * U, elementwise in float, rounded to x_dtype; c % 8 == 0. */
+tlq_status tlq_silu_mul(const void* G, int64_t ldg, const void* U, int64_t ldu, int64_t n_tok, int64_t c,
+                        const tlq_params* p, void* Out, int64_t ldo, void* stream);
+/* Out = H + Z, elementwise in float, rounded to x_dtype; Out may alias H or Z; c % 8 == 0. */
+tlq_status tlq_residual_add(const void* H, int64_t ldh, const void* Z, int64_t ldz, int64_t n_tok,
+                            int64_t c, const tlq_params* p, void* Out, int64_t ldo, void* stream);
+
 /* ---- optional per-kernel timing (host-side bookkeeping only).
  * While enabled, every kernel the library launches is bracketed by HIP events
  * on the launch stream.  tlq_profile_collect waits for the recorded events

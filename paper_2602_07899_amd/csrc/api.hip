@@ -455,4 +455,41 @@ tlq_status tlq_rmsnorm_mul(const void* Z, int64_t n_tok, int64_t c, int64_t ldz,
                                        period, split, X_out, ld_out, (hipStream_t)stream));
 }
 
+// ------------------------------------------------------------ decoder-block glue
+tlq_status tlq_causal_attention(const void* Q, int64_t ldq, const void* K, int64_t ldk, const void* V,
+                                int64_t ldv, int64_t n_tok, int32_t n_heads, int32_t head_dim,
+                                int32_t seq_len, const tlq_params* p, void* Out, int64_t ldo,
+                                void* stream) {
+  if (!Q || !K || !V || !Out) return TLQ_ERR_NULL;
+  TLQ_TRY(check_params(p));
+  if (head_dim != 128) return TLQ_ERR_UNSUPPORTED;
+  if (n_tok <= 0 || n_heads <= 0 || n_heads > 65535 || seq_len <= 0 || seq_len > (1 << 24) ||
+      (n_tok % seq_len) != 0 || n_tok / seq_len > 65535 || n_tok >= (1LL << 31))
+    return TLQ_ERR_SHAPE;
+  const int64_t width = (int64_t)n_heads * 128;
+  if (ldq < width || ldk < width || ldv < width || ldo < width) return TLQ_ERR_SHAPE;
+  if (!mat16_aligned(Q, ldq) || !mat16_aligned(K, ldk) || !mat16_aligned(V, ldv) || !mat16_aligned(Out, ldo))
+    return TLQ_ERR_ALIGN;
+  return hip_status(launch_causal_attention(Q, ldq, K, ldk, V, ldv, n_tok, n_heads, seq_len,
+                                            p->x_dtype == TLQ_BF16, Out, ldo, (hipStream_t)stream));
+}
+
+static tlq_status pairwise(int mode, const void* A, int64_t lda, const void* B, int64_t ldb, int64_t n_tok,
+                           int64_t c, const tlq_params* p, void* Out, int64_t ldo, void* stream) {
+  if (!A || !B || !Out) return TLQ_ERR_NULL;
+  TLQ_TRY(check_params(p));
+  if (!dims_ok(n_tok, c, lda) || ldb < c || ldo < c || (c % 8) != 0) return TLQ_ERR_SHAPE;
+  if (!mat16_aligned(A, lda) || !mat16_aligned(B, ldb) || !mat16_aligned(Out, ldo)) return TLQ_ERR_ALIGN;
+  return hip_status(launch_pairwise(mode, A, lda, B, ldb, n_tok, c, p->x_dtype == TLQ_BF16, Out, ldo,
+                                    (hipStream_t)stream));
+}
+tlq_status tlq_silu_mul(const void* G, int64_t ldg, const void* U, int64_t ldu, int64_t n_tok, int64_t c,
+                        const tlq_params* p, void* Out, int64_t ldo, void* stream) {
+  return pairwise(0, G, ldg, U, ldu, n_tok, c, p, Out, ldo, stream);
+}
+tlq_status tlq_residual_add(const void* H, int64_t ldh, const void* Z, int64_t ldz, int64_t n_tok,
+                            int64_t c, const tlq_params* p, void* Out, int64_t ldo, void* stream) {
+  return pairwise(1, H, ldh, Z, ldz, n_tok, c, p, Out, ldo, stream);
+}
+
 }  // extern "C"

@@ -139,4 +139,12 @@ hipError_t launch_rmsnorm_mul(const void* Z, int64_t ldz, const void* Zb, int64_
                               int64_t c, bool bf16, const float* m_a, const float* m_b, int period,
                               int split, void* out, int64_t ldo, hipStream_t stream);
 
+// decoder-block glue (block.hip): head width 128, rows in blocks of seq_len
+hipError_t launch_causal_attention(const void* Q, int64_t ldq, const void* K, int64_t ldk, const void* V,
+                                   int64_t ldv, int64_t n_tok, int n_heads, int seq_len, bool bf16, void* O,
+                                   int64_t ldo, hipStream_t stream);
+// mode 0: out = SiLU(A) * B; mode 1: out = A + B (c % 8 == 0; out may alias A or B)
+hipError_t launch_pairwise(int mode, const void* A, int64_t lda, const void* B, int64_t ldb, int64_t n_tok,
+                           int64_t c, bool bf16, void* out, int64_t ldo, hipStream_t stream);
+
 }  // namespace tlq

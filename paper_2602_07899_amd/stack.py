@@ -1,0 +1,177 @@
+"""Sequential calibration of a stack of synthetic decoder blocks through libtlq
+(Sec. 3.2.1).  Host-side sequencing only: every tensor operation is a library
+kernel; torch supplies device memory and the concatenation of weight rows for a
+joint search.
+
+Propagation modes (Sec. 3.2.1):
+  "none"      every linear is searched on the full-precision model's activations;
+  "passact1"  two activation streams: x_fp through the full-precision linears,
+              x_q through the quantised ones; searched on x_q against f_fp(x_fp);
+  "passact2"  one stream: each linear sees the output of the quantised linears
+              before it and is compared with the full-precision linear on that input.
+Block: h -> RMSNorm -> q, k, v -> causal attention per sample -> o -> +residual
+-> RMSNorm -> gate, up -> SiLU(gate)*up -> down -> +residual.
+`joint=True` searches linears that share an input (q/k/v, gate/up) with one
+scale vector over their row-concatenated weights.
+A journal (JSON lines, one record per searched group) makes a run resumable:
+groups found in it are not searched again - their recorded grid index is turned
+back into scales (same x_stat and scale-table kernels, so the same bits) and
+only the propagation is redone.
+"""
+from __future__ import annotations
+
+import json
+import os
+
+from . import tlq
+
+LINEARS = ("q_proj", "k_proj", "v_proj", "o_proj", "gate_proj", "up_proj", "down_proj")
+GROUPS = (("q_proj", "k_proj", "v_proj"), ("o_proj",), ("gate_proj", "up_proj"), ("down_proj",))
+
+
+class Journal:
+    """Append-only JSON-lines record of finished searches, keyed by (layer, linear)."""
+
+    def __init__(self, path):
+        self.path = path
+        self.done = {}
+        if path and os.path.exists(path):
+            good = 0
+            with open(path, "rb") as f:
+                for raw in f:
+                    try:
+                        r = json.loads(raw.decode()) if raw.endswith(b"\n") else None
+                    except ValueError:
+                        r = None
+                    if r is None and raw.strip():   # a line cut short by an interrupted run
+                        break
+                    good += len(raw)
+                    if r is not None:
+                        self.done[(r["layer"], r["linear"])] = r
+            if good != os.path.getsize(path):       # drop the damaged tail so that appends stay line-aligned
+                with open(path, "r+b") as f:
+                    f.truncate(good)
+
+    def get(self, layer, name):
+        return self.done.get((layer, name))
+
+    def put(self, rec):
+        self.done[(rec["layer"], rec["linear"])] = rec
+        if self.path:
+            with open(self.path, "a") as f:
+                f.write(json.dumps(rec) + "\n")
+                f.flush()
+                os.fsync(f.fileno())
+
+
+def run_stack(h0, weights_fn, n_layers, token_w, alpha_grid, p, n_heads, seq_len, mode="passact2",
+              joint=False, journal=None, keep=False, on_layer=None):
+    """h0 [n_tok, n_heads*128] device tensor in the activation type; weights_fn(layer)
+    returns the 7 device weight matrices of one block (LINEARS order).  Returns
+    (records, h_q, h_fp): records[layer][linear] holds device tensors best_idx, losses,
+    best_scales (plus X, Y_ref, Z when keep=True); h_q / h_fp are the final hidden
+    states of the quantised / full-precision streams (the same tensor unless
+    mode == "passact1")."""
+    import torch
+    assert mode in ("none", "passact1", "passact2")
+    dev, act = h0.device, h0.dtype
+    n_tok, d = h0.shape
+    assert d == n_heads * 128 and n_tok % seq_len == 0
+    two = mode == "passact1"
+    y_dt = {tlq.F16: torch.float16, tlq.BF16: torch.bfloat16, tlq.F32: torch.float32}[p.yref_dtype]
+    assert y_dt == act, "the full-precision stream is propagated in the activation type"
+    na = alpha_grid.numel()
+    new = lambda cols, dt=act: torch.empty((n_tok, cols), dtype=dt, device=dev)
+    ws_cache = {}
+
+    def workspace(c_in, c_out):
+        need = max(tlq.scale_search_workspace_bytes(n_tok, c_in, c_out, na, p),
+                   tlq.apply_best_workspace_bytes(n_tok, c_in, c_out, p), tlq.x_stat_workspace_bytes(n_tok, c_in))
+        if ws_cache.get("n", 0) < need:
+            ws_cache["t"] = None
+            ws_cache["t"] = torch.empty(need, dtype=torch.uint8, device=dev)
+            ws_cache["n"] = need
+        return ws_cache["t"]
+
+    def search_group(layer, names, Ws, Xq, Xfp, recs):
+        """Returns (Zq list, Zfp list): per-member quantised and full-precision outputs
+        (column slices of one matrix each)."""
+        widths = [W.shape[0] for W in Ws]
+        c_in, tot = Ws[0].shape[1], sum(widths)
+        Y = new(tot, y_dt)
+        offs = [sum(widths[:i]) for i in range(len(Ws))]
+        Ys = [Y[:, o:o + w] for o, w in zip(offs, widths)]
+        for W, Yi in zip(Ws, Ys):
+            tlq.ref_output(Xfp, W, Yi, p)
+        Z = None if mode == "none" else new(tot)
+        units = [(names, torch.cat(Ws, dim=0) if len(Ws) > 1 else Ws[0], Y, Z)] if joint else \
+                [((n,), W, Yi, None if Z is None else Z[:, o:o + w]) for n, W, Yi, o, w in zip(names, Ws, Ys, offs, widths)]
+        for unames, W, Yu, Zu in units:
+            ws = workspace(c_in, W.shape[0])
+            best = torch.empty(c_in, dtype=torch.float32, device=dev)
+            idx = torch.empty(1, dtype=torch.int32, device=dev)
+            losses = torch.empty(na, dtype=torch.float32, device=dev)
+            old = journal.get(layer, unames[0]) if journal is not None else None
+            if old is not None:                                   # resume: rebuild the chosen scales
+                xs = torch.empty(c_in, dtype=torch.float32, device=dev)
+                tlq.x_stat(Xq, p, xs, workspace=ws)
+                tlq.scale_table(xs, alpha_grid[old["best_idx"]:old["best_idx"] + 1], best)
+                idx.fill_(old["best_idx"])
+                losses.copy_(torch.tensor(old["losses"], dtype=torch.float32))
+            else:
+                tlq.scale_search(Xq, W, Yu, token_w, alpha_grid, p, best, idx, losses, workspace=ws)
+                if journal is not None:
+                    li, ll = int(idx.item()), [float(v) for v in losses.tolist()]
+                    for n in unames:
+                        journal.put({"layer": layer, "linear": n, "best_idx": li,
+                                     "alpha": float(alpha_grid[li].item()) if li >= 0 else None, "losses": ll,
+                                     "joint": list(unames) if len(unames) > 1 else None})
+            if Zu is not None:
+                tlq.apply_best(Xq, W, best, p, Zu, workspace=ws)
+            for n in unames:
+                rec = {"best_idx": idx, "losses": losses, "best_scales": best}
+                if keep:
+                    k = names.index(n)
+                    rec.update(X=Xq, Y_ref=Ys[k], Z=None if Z is None else Z[:, offs[k]:offs[k] + widths[k]])
+                recs[n] = rec
+        Zfp = Ys
+        Zq = Zfp if Z is None else [Z[:, o:o + w] for o, w in zip(offs, widths)]
+        return Zq, (Zfp if (two or mode == "none") else Zq)
+
+    hq = h0
+    hf = h0
+    out = []
+    for layer in range(n_layers):
+        Wl = dict(zip(LINEARS, weights_fn(layer)))
+        recs = {}
+        grp = lambda names, xq, xf: search_group(layer, names, [Wl[n] for n in names], xq, xf, recs)
+
+        x1q = tlq.rmsnorm_mul(hq, p, new(d))
+        x1f = tlq.rmsnorm_mul(hf, p, new(d)) if two else x1q
+        zq, zf = grp(GROUPS[0], x1q, x1f)
+        aq = tlq.causal_attention(zq[0], zq[1], zq[2], n_heads, seq_len, p, new(d))
+        af = tlq.causal_attention(zf[0], zf[1], zf[2], n_heads, seq_len, p, new(d)) if two else aq
+        del zq, zf
+        zq, zf = grp(GROUPS[1], aq, af)
+        hq_new = tlq.residual_add(hq, zq[0], p, new(d))
+        hf = tlq.residual_add(hf, zf[0], p, new(d)) if two else hq_new
+        hq = hq_new
+        del zq, zf, aq, af
+        x2q = tlq.rmsnorm_mul(hq, p, new(d))
+        x2f = tlq.rmsnorm_mul(hf, p, new(d)) if two else x2q
+        zq, zf = grp(GROUPS[2], x2q, x2f)
+        f = Wl["gate_proj"].shape[0]
+        mq = tlq.silu_mul(zq[0], zq[1], p, new(f))
+        mf = tlq.silu_mul(zf[0], zf[1], p, new(f)) if two else mq
+        del zq, zf
+        zq, zf = grp(GROUPS[3], mq, mf)
+        hq_new = tlq.residual_add(hq, zq[0], p, new(d))
+        hf = tlq.residual_add(hf, zf[0], p, new(d)) if two else hq_new
+        hq = hq_new
+        del zq, zf, mq, mf
+        if keep:
+            recs["h_out"], recs["h_out_fp"] = hq, hf
+        out.append(recs)
+        if on_layer is not None:
+            on_layer(layer, recs)
+    return out, hq, hf

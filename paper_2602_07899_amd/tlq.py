@@ -65,6 +65,9 @@ _SIGNATURES = {
     "tlq_apply_best_workspace_bytes": (_SZ, [_I64, _I64, _I64, _PP]),
     "tlq_apply_best": (C.c_int, [_P, _I64, _I64, _I64, _P, _I64, _I64, _P, _PP, _P, _I64, _P, _SZ, _P]),
     "tlq_rmsnorm_mul": (C.c_int, [_P, _I64, _I64, _I64, _P, _I64, _P, _P, _I32, _I32, _PP, _P, _I64, _P]),
+    "tlq_causal_attention": (C.c_int, [_P, _I64, _P, _I64, _P, _I64, _I64, _I32, _I32, _I32, _PP, _P, _I64, _P]),
+    "tlq_silu_mul": (C.c_int, [_P, _I64, _P, _I64, _I64, _I64, _PP, _P, _I64, _P]),
+    "tlq_residual_add": (C.c_int, [_P, _I64, _P, _I64, _I64, _I64, _PP, _P, _I64, _P]),
     "tlq_profile_enable": (C.c_int, [C.c_int]),
     "tlq_profile_reset": (C.c_int, []),
     "tlq_profile_collect": (C.c_int, []),
@@ -237,6 +240,28 @@ def rmsnorm_mul(Z, p, X_out, Zb=None, m_a=None, m_b=None, period=0, split=0):
                                  _ptr(m_b), period, split, C.byref(p), _ptr(X_out), _ld(X_out), _stream()),
            "tlq_rmsnorm_mul")
     return X_out
+
+
+def causal_attention(Q, K, V, n_heads, seq_len, p, Out):
+    """Q, K, V, Out: [n_tok, >= n_heads*128] (column slices of a wider matrix are fine)."""
+    _check(lib().tlq_causal_attention(_ptr(Q), _ld(Q), _ptr(K), _ld(K), _ptr(V), _ld(V), Q.shape[0], n_heads,
+                                      128, seq_len, C.byref(p), _ptr(Out), _ld(Out), _stream()),
+           "tlq_causal_attention")
+    return Out
+
+
+def silu_mul(G, U, p, Out):
+    n, c = G.shape
+    _check(lib().tlq_silu_mul(_ptr(G), _ld(G), _ptr(U), _ld(U), n, c, C.byref(p), _ptr(Out), _ld(Out), _stream()),
+           "tlq_silu_mul")
+    return Out
+
+
+def residual_add(H, Z, p, Out):
+    n, c = H.shape
+    _check(lib().tlq_residual_add(_ptr(H), _ld(H), _ptr(Z), _ld(Z), n, c, C.byref(p), _ptr(Out), _ld(Out),
+                                  _stream()), "tlq_residual_add")
+    return Out
 
 
 # ------------------------------------------------------------------ profiling

@@ -91,6 +91,71 @@ CONFIGS = {
 }
 
 
+@dataclass(frozen=True)
+class StackWorkload:
+    """A stack of synthetic decoder blocks calibrated in sequence: hidden width
+    n_heads*128, every block holding the 7 linears q, k, v, o, gate, up, down."""
+    name: str
+    n_layers: int
+    n_heads: int
+    ffn: int
+    n_samples: int
+    n_vis: int
+    n_txt: int
+    bits: tuple = (4, 3)
+    group: int = 128
+    n_alpha: int = 20
+    seed: int = 0
+    w_std: float = 0.02
+    n_outlier: int | None = None
+    outlier_frac: float = 0.01
+    txt_mult: float = 30.0
+    vis_mult: float = 5.0
+    act_dtype: str = "bf16"
+
+    @property
+    def hidden(self) -> int:
+        return self.n_heads * 128
+
+    @property
+    def seq_len(self) -> int:
+        return self.n_vis + self.n_txt
+
+    @property
+    def n_tok(self) -> int:
+        return self.n_samples * self.seq_len
+
+    def shapes(self) -> tuple:
+        d, f = self.hidden, self.ffn
+        return ((d, d), (d, d), (d, d), (d, d), (f, d), (f, d), (d, f))
+
+    def as_workload(self) -> Workload:
+        """The token/importance recipe of the stack's embedding, as a one-linear workload."""
+        return Workload(self.name, (LinearSpec("embed", self.hidden, self.hidden),), n_samples=self.n_samples,
+                        n_vis=self.n_vis, n_txt=self.n_txt, seed=self.seed, n_outlier=self.n_outlier,
+                        outlier_frac=self.outlier_frac, txt_mult=self.txt_mult, vis_mult=self.vis_mult)
+
+
+STACKS = {
+    # 13B-class: 40 blocks, hidden 5120 (40 heads), ffn 13824, 128 samples x 1200 tokens, bf16, W4 then W3
+    "cfg5_13b_stack": StackWorkload("cfg5_13b_stack", n_layers=40, n_heads=40, ffn=13824, n_samples=128,
+                                    n_vis=1152, n_txt=48),
+    # scaled-down stack for full-oracle parity: 2 blocks, hidden 256 (2 heads), ffn 384, 3 x 72 tokens
+    "cfg5_mini_stack": StackWorkload("cfg5_mini_stack", n_layers=2, n_heads=2, ffn=384, n_samples=3, n_vis=48,
+                                     n_txt=24, n_alpha=6, n_outlier=3, w_std=0.06),
+}
+
+
+def make_stack_weights(sw: StackWorkload, layer: int) -> list:
+    """The 7 weight matrices of one block, float32 values ~ N(0, w_std^2) (the caller
+    rounds them to the activation type); seeded per (stack seed * 1000 + layer, linear)."""
+    out = []
+    for li, (co, ci) in enumerate(sw.shapes()):
+        g = _rng(sw.seed * 1000 + layer, 2000 + li, 0)
+        out.append(g.standard_normal((co, ci), dtype=np.float32) * np.float32(sw.w_std))
+    return out
+
+
 def _rng(seed: int, stream: int, index: int) -> np.random.Generator:
     return np.random.default_rng([int(seed), int(stream), int(index)])
 

@@ -101,6 +101,22 @@ def test_other_entry_points_reject_bad_arguments():
     assert l.tlq_rmsnorm_mul(None, 4, 8, 8, None, 0, None, None, 0, 0, bp, FAKE, 8, None) == tlq.ERR_NULL
     assert l.tlq_rmsnorm_mul(FAKE, 4, 8, 8, None, 0, None, None, 0, 0, bp, FAKE, 4, None) == tlq.ERR_SHAPE
     assert l.tlq_rmsnorm_mul(FAKE, 4, 8, 8, None, 0, None, None, 4, 2, bp, FAKE, 8, None) == tlq.ERR_SHAPE
+    att = lambda **k: l.tlq_causal_attention(k.get("Q", FAKE), k.get("ld", 256), FAKE, 256, FAKE, 256, k.get("n", 64),
+                                             k.get("heads", 2), k.get("dh", 128), k.get("seq", 32), bp,
+                                             k.get("out", FAKE), k.get("ldo", 256), None)
+    assert att(Q=None) == tlq.ERR_NULL and att(out=None) == tlq.ERR_NULL
+    assert att(dh=64) == tlq.ERR_UNSUPPORTED
+    assert att(seq=48) == tlq.ERR_SHAPE            # 64 tokens are not whole samples of 48
+    assert att(seq=0) == tlq.ERR_SHAPE and att(heads=0) == tlq.ERR_SHAPE and att(n=0) == tlq.ERR_SHAPE
+    assert att(ld=128) == tlq.ERR_SHAPE and att(ldo=200) == tlq.ERR_SHAPE      # narrower than heads*128
+    assert att(Q=ODD) == tlq.ERR_ALIGN and att(ld=260) == tlq.ERR_ALIGN
+    for fn in (l.tlq_silu_mul, l.tlq_residual_add):
+        assert fn(None, 8, FAKE, 8, 4, 8, bp, FAKE, 8, None) == tlq.ERR_NULL
+        assert fn(FAKE, 8, FAKE, 8, 4, 8, bp, None, 8, None) == tlq.ERR_NULL
+        assert fn(FAKE, 16, FAKE, 16, 4, 12, bp, FAKE, 16, None) == tlq.ERR_SHAPE   # width not a multiple of 8
+        assert fn(FAKE, 8, FAKE, 4, 4, 8, bp, FAKE, 8, None) == tlq.ERR_SHAPE
+        assert fn(FAKE, 8, FAKE, 8, 0, 8, bp, FAKE, 8, None) == tlq.ERR_SHAPE
+        assert fn(ODD, 8, FAKE, 8, 4, 8, bp, FAKE, 8, None) == tlq.ERR_ALIGN
 
 
 def test_workspace_queries():

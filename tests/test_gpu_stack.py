@@ -1,0 +1,223 @@
+"""Decoder-stack sequential calibration on the GPU against the stack oracle:
+the block glue kernels element by element, the three propagation modes and the
+joint shared-input search on a scaled-down stack (bf16 activations), and the
+resumable journal."""
+import json
+import os
+
+import numpy as np
+import pytest
+
+from oracle import stack as ost
+from oracle import tlq_oracle as orc
+from paper_2602_07899_amd import stack as gstack
+from paper_2602_07899_amd import tlq
+from paper_2602_07899_amd import workloads as wl
+
+pytestmark = pytest.mark.gpu
+
+BF = lambda a: orc.round_to_bf16(np.asarray(a, np.float64).astype(np.float32))
+F16 = lambda a: np.asarray(a, np.float64).astype(np.float16)
+
+
+def dev(a, gpu, bf16):
+    import torch
+    t = torch.from_numpy(np.ascontiguousarray(np.asarray(a, np.float32)))
+    return t.to(torch.bfloat16 if bf16 else torch.float16).to(gpu)
+
+
+def host(t):
+    return t.detach().float().cpu().numpy().astype(np.float64)
+
+
+@pytest.mark.parametrize("bf16", [False, True])
+@pytest.mark.parametrize("seq,heads,samples", [(300, 3, 2), (129, 1, 3), (32, 2, 1), (1, 1, 4), (77, 2, 2)])
+def test_causal_attention_parity(gpu, bf16, seq, heads, samples):
+    import torch
+    g = np.random.default_rng([11, seq, heads])
+    rnd = BF if bf16 else F16
+    n, width = seq * samples, heads * 128
+    qkv = np.asarray(rnd(g.standard_normal((n, 3 * width)) * 1.5), np.float64)
+    q, k, v = qkv[:, :width], qkv[:, width:2 * width], qkv[:, 2 * width:]
+    want = ost.causal_attention(q, k, v, heads, seq)
+    # sum_j p_j |v_j| bounds what rounding the probabilities can do
+    mag = ost.causal_attention(q, k, np.abs(v), heads, seq)
+    p = tlq.params(x_dtype=tlq.BF16 if bf16 else tlq.F16)
+    t = dev(qkv, gpu, bf16)                      # q, k, v as column slices of one matrix
+    out = torch.full((n, width + 8), 7.0, dtype=t.dtype, device=gpu)
+    tlq.causal_attention(t[:, :width], t[:, width:2 * width], t[:, 2 * width:], heads, seq, p, out[:, :width])
+    torch.cuda.synchronize()
+    got = host(out)
+    assert np.all(got[:, width:] == 7.0)         # nothing written outside the heads
+    eps = 2.0 ** -8 if bf16 else 2.0 ** -11
+    err = np.abs(got[:, :width] - want)
+    assert np.all(err <= eps * (mag + np.abs(want)) + 2e-6), float((err / (eps * (mag + np.abs(want)) + 2e-6)).max())
+    # well inside the bound on average: the probabilities' rounding errors do not line up
+    assert err.mean() <= 0.3 * eps * (mag + np.abs(want)).mean()
+
+
+def test_causal_attention_peaked_scores(gpu):
+    """Large scores (softmax close to one-hot): the running-maximum rescaling must hold."""
+    import torch
+    g = np.random.default_rng(12)
+    seq, heads = 200, 2
+    q = F16(g.standard_normal((seq, heads * 128)) * 6.0)
+    k = F16(g.standard_normal((seq, heads * 128)) * 6.0)
+    v = F16(g.standard_normal((seq, heads * 128)))
+    want = ost.causal_attention(q, k, v, heads, seq)
+    mag = ost.causal_attention(q, k, np.abs(v.astype(np.float64)), heads, seq)
+    p = tlq.params()
+    out = torch.empty((seq, heads * 128), dtype=torch.float16, device=gpu)
+    tlq.causal_attention(dev(q, gpu, False), dev(k, gpu, False), dev(v, gpu, False), heads, seq, p, out)
+    err = np.abs(host(out) - want)
+    # exp of a float score of magnitude ~50 carries ~50 ulp of relative error
+    assert np.all(err <= (2.0 ** -11 + 2e-5) * (mag + np.abs(want)) + 2e-6)
+
+
+@pytest.mark.parametrize("bf16", [False, True])
+def test_silu_mul_and_residual_add_parity(gpu, bf16):
+    import torch
+    g = np.random.default_rng(13)
+    rnd = BF if bf16 else F16
+    n, c = 37, 264
+    a = np.asarray(rnd(g.standard_normal((n, c)) * 4.0), np.float64)
+    b = np.asarray(rnd(g.standard_normal((n, c))), np.float64)
+    p = tlq.params(x_dtype=tlq.BF16 if bf16 else tlq.F16)
+    ta, tb = dev(a, gpu, bf16), dev(b, gpu, bf16)
+    wide = torch.zeros((n, c + 16), dtype=ta.dtype, device=gpu)
+    eps = 2.0 ** -8 if bf16 else 2.0 ** -11
+    tlq.silu_mul(ta, tb, p, wide[:, 8:8 + c])
+    want = ost.silu_mul(a, b)
+    got = host(wide)
+    assert np.all(got[:, :8] == 0) and np.all(got[:, 8 + c:] == 0)
+    assert np.all(np.abs(got[:, 8:8 + c] - want) <= eps * np.abs(want) * 1.001 + 1e-7 + 2e-6 * np.abs(want))   # half an ulp of storage
+    tlq.residual_add(ta, tb, p, ta)              # in place
+    want = np.asarray(rnd(a + b), np.float64)
+    np.testing.assert_array_equal(host(ta), want)   # one float addition, one rounding: exact
+
+
+# ------------------------------------------------------------------ the stack
+def _mini(gpu):
+    import torch
+    sw = wl.STACKS["cfg5_mini_stack"]
+    base = sw.as_workload()
+    h0 = BF(np.concatenate([wl.make_sample_tokens(base, 0, b) for b in range(sw.n_samples)], axis=0))
+    Ws = [[BF(W) for W in wl.make_stack_weights(sw, l)] for l in range(sw.n_layers)]
+    w = wl.make_token_weights(base, 0)
+    al = wl.alpha_grid(sw.n_alpha)
+    tW = [[dev(W, gpu, True) for W in layer] for layer in Ws]
+    return sw, h0, Ws, w, al, tW
+
+
+def _gpu_run(gpu, sw, h0, tW, w, al, bits, mode, joint, journal=None, keep=True, n_layers=None):
+    import torch
+    p = tlq.params(bits=bits, group=sw.group, x_dtype=tlq.BF16, yref_dtype=tlq.BF16)
+    return gstack.run_stack(dev(h0, gpu, True), lambda l: tW[l], n_layers or sw.n_layers,
+                            torch.from_numpy(w).to(gpu), torch.from_numpy(al).to(gpu), p, sw.n_heads,
+                            sw.seq_len, mode=mode, joint=joint, journal=journal, keep=keep)
+
+
+@pytest.mark.parametrize("mode,joint", [("passact2", False), ("passact1", False), ("none", False),
+                                        ("passact2", True), ("passact1", True)])
+def test_stack_teacher_forced_parity(gpu, mode, joint):
+    """Every search of the oracle's stack run is repeated on the GPU with the ORACLE's
+    exposed input and target (so an upstream one-ulp difference cannot hide or fake a
+    mismatch), then the glue after it is checked on the oracle's tensors."""
+    import torch
+    sw, h0, Ws, w, al, tW = _mini(gpu)
+    bits = 4
+    recs = ost.run_stack(h0, Ws, w, bits, sw.group, al, sw.n_heads, sw.seq_len, BF, mode=mode, joint=joint)
+    p = tlq.params(bits=bits, group=sw.group, x_dtype=tlq.BF16, yref_dtype=tlq.BF16)
+    tw, tal = torch.from_numpy(w).to(gpu), torch.from_numpy(al).to(gpu)
+    for l, layer in enumerate(recs):
+        for names in gstack.GROUPS:
+            units = [names] if joint else [(n,) for n in names]
+            for un in units:
+                X = layer[un[0]]["X"]
+                W = np.concatenate([Ws[l][ost.LINEARS.index(n)] for n in un], axis=0)
+                Y = np.concatenate([layer[n]["Y_ref"] for n in un], axis=1)
+                res = layer[un[0]]["res"]
+                ci = X.shape[1]
+                best = torch.empty(ci, dtype=torch.float32, device=gpu)
+                idx = torch.empty(1, dtype=torch.int32, device=gpu)
+                losses = torch.empty(al.size, dtype=torch.float32, device=gpu)
+                tlq.scale_search(dev(X, gpu, True), dev(W, gpu, True), dev(Y, gpu, True), tw, tal, p, best, idx, losses)
+                gl, ol = losses.cpu().numpy().astype(np.float64), np.asarray(res["losses"], np.float64)
+                rel = np.abs(gl - ol) / ol
+                assert rel.max() < 1e-3, (l, un, rel.max())
+                if int(idx.item()) != res["best_idx"]:
+                    srt = np.sort(ol)
+                    assert (srt[1] - srt[0]) / srt[0] < 1e-3, (l, un)
+    # glue on the oracle's tensors: attention input of o_proj, SiLU gate input of down_proj, residual
+    r0 = recs[0]
+    pq = tlq.params(x_dtype=tlq.BF16)
+    if mode != "none":
+        zq, zk, zv = (r0[n]["Z"] for n in ("q_proj", "k_proj", "v_proj"))
+    else:
+        zq, zk, zv = (r0[n]["Y_ref"] for n in ("q_proj", "k_proj", "v_proj"))
+    out = torch.empty((h0.shape[0], sw.hidden), dtype=torch.bfloat16, device=gpu)
+    tlq.causal_attention(dev(zq, gpu, True), dev(zk, gpu, True), dev(zv, gpu, True), sw.n_heads, sw.seq_len, pq, out)
+    want = np.asarray(r0["o_proj"]["X"], np.float64)
+    mag = ost.causal_attention(zq, zk, np.abs(np.asarray(zv, np.float64)), sw.n_heads, sw.seq_len)
+    assert np.all(np.abs(host(out) - want) <= 2.0 ** -8 * (mag + np.abs(want)) + 1e-6)
+
+
+@pytest.mark.parametrize("mode,joint", [("passact2", False), ("passact1", False), ("none", False), ("passact2", True)])
+def test_stack_free_running(gpu, mode, joint):
+    """The GPU driver on its own against the oracle's run: a one-ulp difference upstream may
+    flip a few quantisation codes, so the comparison is looser than the teacher-forced one."""
+    sw, h0, Ws, w, al, tW = _mini(gpu)
+    bits = 4
+    recs = ost.run_stack(h0, Ws, w, bits, sw.group, al, sw.n_heads, sw.seq_len, BF, mode=mode, joint=joint)
+    out, hq, hf = _gpu_run(gpu, sw, h0, tW, w, al, bits, mode, joint)
+    for l, (g, o) in enumerate(zip(out, recs)):
+        for n in ost.LINEARS:
+            gl = g[n]["losses"].cpu().numpy().astype(np.float64)
+            ol = np.asarray(o[n]["res"]["losses"], np.float64)
+            assert np.abs(gl - ol).max() / ol.max() < 2e-2, (l, n)
+            if int(g[n]["best_idx"].item()) != o[n]["res"]["best_idx"]:
+                srt = np.sort(ol)
+                assert (srt[1] - srt[0]) / srt[0] < 2e-2, (l, n)
+            xo = np.asarray(o[n]["X"], np.float64)
+            dx = host(g[n]["X"]) - xo
+            assert np.linalg.norm(dx) <= 2e-2 * np.linalg.norm(xo), (l, n)
+            assert np.abs(dx).max() <= 0.1 * np.abs(xo).max(), (l, n)
+    ho = np.asarray(recs[-1]["h_out"], np.float64)
+    assert np.linalg.norm(host(hq) - ho) <= 2e-2 * np.linalg.norm(ho)
+    hfo = np.asarray(recs[-1]["h_out_fp"], np.float64)
+    assert np.linalg.norm(host(hf) - hfo) <= 2e-2 * np.linalg.norm(hfo)
+    if mode == "passact1":
+        assert hq.data_ptr() != hf.data_ptr()
+        # the full-precision stream does not depend on any quantisation: it equals the "none" run's
+        _, hn, _ = _gpu_run(gpu, sw, h0, tW, w, al, bits, "none", False)
+        assert bool((hn == hf).all())
+
+
+def test_stack_journal_resume(gpu, tmp_path):
+    import torch
+    sw, h0, Ws, w, al, tW = _mini(gpu)
+    path = str(tmp_path / "journal.jsonl")
+    full, hq, _ = _gpu_run(gpu, sw, h0, tW, w, al, 3, "passact2", False, journal=gstack.Journal(path))
+    lines = open(path).read().splitlines()
+    assert len(lines) == 7 * sw.n_layers
+    rec0 = json.loads(lines[0])
+    assert rec0["layer"] == 0 and rec0["linear"] == "q_proj" and len(rec0["losses"]) == al.size
+    # an interrupted run: five finished searches and a line cut short
+    with open(path, "w") as f:
+        f.write("\n".join(lines[:5]) + "\n" + lines[5][: len(lines[5]) // 2])
+    tlq.profile_reset()
+    tlq.profile_enable(True)
+    j = gstack.Journal(path)
+    assert len(j.done) == 5
+    again, hq2, _ = _gpu_run(gpu, sw, h0, tW, w, al, 3, "passact2", False, journal=j)
+    torch.cuda.synchronize()
+    tlq.profile_enable(False)
+    launches = {k.name: k.launches for k in tlq.profile_read()}
+    assert launches.get("gemm_loss", 0) == 7 * sw.n_layers - 5        # finished searches are not repeated
+    assert bool((hq == hq2).all())
+    for a, b in zip(full, again):
+        for n in ost.LINEARS:
+            assert int(a[n]["best_idx"].item()) == int(b[n]["best_idx"].item())
+            assert bool((a[n]["best_scales"] == b[n]["best_scales"]).all())
+            assert bool((a[n]["losses"] == b[n]["losses"]).all())
+    assert len(gstack.Journal(path).done) == 7 * sw.n_layers
