@@ -1,0 +1,136 @@
+"""Run the sequential calibration of a synthetic decoder stack on one GPU and
+report wall time, split into search and glue.
+
+    python -m paper_2602_07899_amd.run_stack --stack cfg5_13b_stack --bits 4
+
+Inputs are drawn on the device (torch's counter-based generator, seeded per
+stack and per block), with the same structure as the host recipe of
+`workloads.py`: N(0,1) embeddings with a fixed 1 % of outlier channels scaled
+x5 on visual rows and x30 on text rows, N(0, w_std^2) weights, heavy-tailed
+token weights.  One progress line per block; the last line is a JSON summary.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import sys
+import time
+
+import numpy as np
+
+from . import stack as gstack
+from . import tlq
+from . import workloads as wl
+
+SEARCH_KERNELS = ("xstat_partial", "xstat_final", "scale_table", "fake_quant", "gemm_loss", "finalize", "bf16_to_f16",
+                  "act_quant")
+BLOCK_KERNELS = ("rmsnorm_mul", "causal_attention", "silu_mul", "residual_add")
+
+
+def device_inputs(sw, dev, dtype, n_samples=None):
+    """h0 [n_tok, hidden] and token weights [n_tok] on the device."""
+    import torch
+    ns = n_samples or sw.n_samples
+    per, d = sw.seq_len, sw.hidden
+    g = torch.Generator(device=dev)
+    g.manual_seed(sw.seed * 1000 + 999)
+    h = torch.randn((ns * per, d), generator=g, device=dev, dtype=torch.float32)
+    oc = torch.from_numpy(wl.outlier_channels(sw.as_workload(), 0)).to(dev)
+    is_txt = (torch.arange(ns * per, device=dev) % per) >= sw.n_vis
+    mult = torch.where(is_txt, sw.txt_mult, sw.vis_mult).to(torch.float32)
+    h[:, oc] *= mult[:, None]
+    w = torch.exp(torch.randn(ns * per, generator=g, device=dev, dtype=torch.float32))
+    w = torch.where(is_txt, 4.0 * w, w).double()
+    return h.to(dtype), (w / w.sum()).float()
+
+
+def device_weights(sw, dev, dtype):
+    import torch
+
+    def fn(layer):
+        g = torch.Generator(device=dev)
+        g.manual_seed(sw.seed * 1000 + layer)
+        return [(torch.randn(s, generator=g, device=dev, dtype=torch.float32) * sw.w_std).to(dtype)
+                for s in sw.shapes()]
+    return fn
+
+
+def run(stack_name, bits, mode="passact2", joint=False, n_layers=None, n_samples=None, journal_path=None,
+        act_bits=0, log=print):
+    import torch
+    if not torch.cuda.is_available():
+        raise RuntimeError("run_stack needs a GPU")
+    dev = torch.device("cuda:0")
+    sw = wl.STACKS[stack_name]
+    bf16 = sw.act_dtype == "bf16"
+    dtype = torch.bfloat16 if bf16 else torch.float16
+    code = tlq.BF16 if bf16 else tlq.F16
+    p = tlq.params(bits=bits, group=sw.group, x_dtype=code, yref_dtype=code, act_bits=act_bits)
+    layers = n_layers or sw.n_layers
+    h0, w = device_inputs(sw, dev, dtype, n_samples)
+    al = torch.from_numpy(wl.alpha_grid(sw.n_alpha)).to(dev)
+    journal = gstack.Journal(journal_path) if journal_path else None
+    tlq.profile_reset()
+    tlq.profile_enable(True)
+    torch.cuda.synchronize()
+    t0 = time.time()
+    summary = []
+
+    def on_layer(layer, recs):
+        # one small device-to-host read per block: it is the progress line
+        idx = [int(recs[n]["best_idx"].item()) for n in gstack.LINEARS]
+        ls = [recs[n]["losses"].tolist() for n in gstack.LINEARS]
+        summary.append({"layer": layer, "best_idx": idx, "losses": ls})
+        log(f"[run_stack] W{bits} {mode} block {layer + 1}/{layers} done at {time.time() - t0:7.2f} s  best_idx={idx}")
+        sys.stdout.flush()
+
+    _, hq, hf = gstack.run_stack(h0, device_weights(sw, dev, dtype), layers, w, al, p, sw.n_heads, sw.seq_len,
+                                 mode=mode, joint=joint, journal=journal, on_layer=on_layer)
+    torch.cuda.synchronize()
+    wall = time.time() - t0
+    tlq.profile_enable(False)
+    prof = {k.name: k for k in tlq.profile_read()}
+    search_ms = sum(k.total_ms for n, k in prof.items() if n in SEARCH_KERNELS)
+    block_ms = sum(k.total_ms for n, k in prof.items() if n in BLOCK_KERNELS)
+    prop_ms = sum(k.total_ms for n, k in prof.items() if n not in SEARCH_KERNELS and n not in BLOCK_KERNELS)
+    gl = prof.get("gemm_loss")
+    n_search = gl.launches if gl else 0
+    out = {
+        "stack": stack_name, "bits": bits, "mode": mode, "joint": joint, "act_bits": act_bits, "layers": layers,
+        "n_tok": int(h0.shape[0]), "hidden": sw.hidden, "ffn": sw.ffn, "dtype": sw.act_dtype,
+        # search = S0..S5; propagate = full-precision targets and the quantised outputs fed forward (S6);
+        # block = the decoder block between the linears; the rest is weight generation and host time
+        "wall_s": wall, "search_kernels_s": search_ms / 1e3, "propagate_kernels_s": prop_ms / 1e3,
+        "block_kernels_s": block_ms / 1e3, "other_s": wall - (search_ms + prop_ms + block_ms) / 1e3,
+        "evals": n_search * sw.n_alpha if not joint else None,
+        "evals_per_s": (7 * layers * sw.n_alpha) / wall,
+        "gemm_loss_tflops": (gl.total_work / (gl.total_ms * 1e-3) / 1e12) if gl and gl.total_ms > 0 else None,
+        "kernels": {n: {"launches": k.launches, "ms": round(k.total_ms, 3)} for n, k in prof.items()},
+        "h_finite": bool(torch.isfinite(hq.float()).all().item()),
+        "h_rms": float(hq.float().pow(2).mean().sqrt().item()),
+        "stream_gap_rel": float(((hq.float() - hf.float()).norm() / hf.float().norm()).item()),
+        "blocks": summary,
+    }
+    return out
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--stack", default="cfg5_13b_stack", choices=sorted(wl.STACKS))
+    ap.add_argument("--bits", type=int, default=4)
+    ap.add_argument("--mode", default="passact2", choices=("none", "passact1", "passact2"))
+    ap.add_argument("--joint", action="store_true")
+    ap.add_argument("--layers", type=int, default=None)
+    ap.add_argument("--samples", type=int, default=None)
+    ap.add_argument("--act-bits", type=int, default=0)
+    ap.add_argument("--journal", default=None)
+    ap.add_argument("--brief", action="store_true", help="leave the per-block records out of the summary")
+    a = ap.parse_args()
+    out = run(a.stack, a.bits, a.mode, a.joint, a.layers, a.samples, a.journal, a.act_bits)
+    if a.brief:
+        out.pop("blocks")
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()

@@ -221,3 +221,24 @@ def test_stack_journal_resume(gpu, tmp_path):
             assert bool((a[n]["best_scales"] == b[n]["best_scales"]).all())
             assert bool((a[n]["losses"] == b[n]["losses"]).all())
     assert len(gstack.Journal(path).done) == 7 * sw.n_layers
+
+
+def test_stack_full_size_block_properties(gpu):
+    """One block of the 13B-class stack at its full 153,600 tokens (bf16, W3), launched exactly as
+    the stack runner launches it; checked through properties that hold at any size."""
+    from paper_2602_07899_amd import run_stack
+    out = run_stack.run("cfg5_13b_stack", 3, n_layers=1, log=lambda *_: None)
+    assert out["n_tok"] == 153600 and out["h_finite"] and out["evals"] == 140
+    blk = out["blocks"][0]
+    for n, bi, ls in zip(gstack.LINEARS, blk["best_idx"], blk["losses"]):
+        ls = np.asarray(ls)
+        assert np.all(np.isfinite(ls)) and np.all(ls > 0), n
+        assert 0 <= bi < 20 and ls[bi] == ls.min() and ls[bi] <= ls[0], n
+        # the normalised hidden state carries the outlier channels: there a moderate alpha is clearly
+        # better than none and than alpha close to 1 (attention and gate outputs have none)
+        if n in ("q_proj", "k_proj", "v_proj", "gate_proj", "up_proj"):
+            assert ls.min() < 0.95 * ls[0] and ls.min() < 0.95 * ls[-1], n
+    # q, k, v share their input: same x_stat, so nearly the same loss curves
+    q, k = np.asarray(blk["losses"][0]), np.asarray(blk["losses"][1])
+    assert np.abs(q - k).max() < 0.02 * q.max()
+    assert out["kernels"]["gemm_loss"]["launches"] == 7 and out["kernels"]["causal_attention"]["launches"] == 1
