@@ -139,6 +139,23 @@ def main():
     tlq.profile_enable(False)
     kernels = {k.name: k for k in tlq.profile_read()}
 
+    # per linear shape (outside the timed region): median of 3 searches, events on the launch stream
+    per_linear = []
+    for spec, X, W, Y, w, (best, idx, losses) in layers:
+        ms = []
+        for _ in range(3):
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0.record()
+            tlq.scale_search(X, W, Y, w, al, p, best, idx, losses, workspace=workspace)
+            e1.record()
+            e1.synchronize()
+            ms.append(e0.elapsed_time(e1))
+        m = sorted(ms)[1]
+        per_linear.append({"linear": f"{spec.name}:{spec.c_out}x{spec.c_in}", "ms_per_search": round(m, 4),
+                           "evals_per_s": workload.n_alpha / (m * 1e-3),
+                           "search_tflops": 2.0 * workload.n_tok * spec.c_in * spec.c_out * workload.n_alpha
+                                            / (m * 1e-3) / 1e12})
+
     evals = len(layers) * workload.n_alpha * args.steps
     g = kernels["gemm_loss"]
     tflops = g.total_work / (g.total_ms * 1e-3) / 1e12
@@ -163,6 +180,7 @@ def main():
                              "rate": (k.total_work / (k.total_ms * 1e-3) / 1e9) if k.total_ms > 0 else None,
                              "rate_unit": "GFLOP/s" if k.name.startswith("gemm") else "GB/s"}
                     for k in kernels.values()},
+        "per_linear": per_linear,
         "best_alpha_index": best_idx,
     }
     if not args.no_ceiling:
