@@ -175,7 +175,7 @@ def main():
         "roofline": {"bound": "mfma", "kernel": "gemm_loss", "achieved": tflops, "peak": PEAK_FP16_TFLOPS,
                      "unit": "TFLOP/s", "frac": tflops / PEAK_FP16_TFLOPS,
                      "avg_launch_ms": g.total_ms / g.launches, "flops_per_launch": flops_per_launch,
-                     "traffic": MEASURED_TRAFFIC_BYTES_PER_LAUNCH},
+                     "traffic": MEASURED_TRAFFIC_BYTES_PER_LAUNCH if args.act_bits == 0 else None},
         "kernels": {k.name: {"launches": k.launches, "ms": round(k.total_ms, 4),
                              "rate": (k.total_work / (k.total_ms * 1e-3) / 1e9) if k.total_ms > 0 else None,
                              "rate_unit": "GFLOP/s" if k.name.startswith("gemm") else "GB/s"}
