@@ -193,7 +193,7 @@ tlq_status tlq_apply_best(const void* X, int64_t n_tok, int64_t c_in, int64_t ld
                           const tlq_params* p, void* X_next, int64_t ld_next,
                           void* workspace, size_t workspace_bytes, void* stream);
 
-/* ---- glue of the synthetic sequential chain (not the paper's method):
+/* ---- glue of the synthetic sequential chain (the workload's construction, not the paper's method):
  * builds the exposed input of the next linear from the quantised output of the
  * previous one (Sec. 3.2.1 PassAct2 propagation).
  *   v = Z (or Z*Zb elementwise when Zb != NULL);
