@@ -146,6 +146,61 @@ __device__ __forceinline__ void loss_rows(const GemmDev& a, f32x16 (&acc)[FA][FB
   }
 }
 
+// Same sums as loss_rows for an interior wave tile with 16-bit Y_ref, but Y_ref goes through
+// LDS: the wave copies its 64-token x 128-row piece with whole-line loads (each 128-byte line
+// is fetched once, 8 lines per instruction) into `ylds` (WT x WO 16-bit, this wave's own),
+// then every lane picks its values from there.  Reading Y_ref straight from the accumulator
+// layout touches 32 lines per instruction and each line 8 times.  16-byte chunks of a token
+// row are stored at chunk ^ (token % 16), which makes the 8-byte reads conflict-free.
+template <typename YT, int FA, int FB>
+__device__ __forceinline__ void loss_rows_lds(const GemmDev& a, f32x16 (&acc)[FA][FB], const float* tsc,
+                                              int64_t ow, int64_t tw, float (&sq)[FB], float& part,
+                                              unsigned char* ylds) {
+  constexpr int WO = FA * 32, WT = FB * 32;
+  constexpr int CPR = WO / 8;              // 16-byte chunks per token row
+  constexpr int RPI = 64 / CPR;            // token rows per wave-wide copy
+  static_assert(CPR == 16 && WT % RPI == 0, "copy shape");
+  const int lane = threadIdx.x & 63, frow = lane & 31, fhi = lane >> 5;
+  const uint16_t* Y = (const uint16_t*)a.Yref;
+  {
+    const int cr = lane / CPR, cc = lane % CPR;
+    uint4 v[WT / RPI];
+#pragma unroll
+    for (int j = 0; j < WT / RPI; ++j) {
+      const int row = j * RPI + cr;
+      v[j] = *reinterpret_cast<const uint4*>(Y + (tw + row) * a.ldy + ow + cc * 8);
+    }
+#pragma unroll
+    for (int j = 0; j < WT / RPI; ++j) {
+      const int row = j * RPI + cr;
+      *reinterpret_cast<uint4*>(ylds + row * (WO * 2) + ((cc ^ (row & 15)) << 4)) = v[j];
+    }
+  }
+#pragma unroll
+  for (int j = 0; j < FB; ++j) {
+    const int tok = j * 32 + frow;
+    const int64_t t = tw + tok;
+    const float nsg = tsc ? -tsc[t] : -1.0f;
+    float sumsq = 0.0f;
+#pragma unroll
+    for (int i = 0; i < FA; ++i)
+#pragma unroll
+      for (int q = 0; q < 4; ++q) {
+        const uint2 u = *reinterpret_cast<const uint2*>(ylds + tok * (WO * 2) +
+                                                        (((i * 4 + q) ^ (tok & 15)) << 4) + fhi * 8);
+        const float y[4] = {YT::to_float((uint16_t)(u.x & 0xffffu)), YT::to_float((uint16_t)(u.x >> 16)),
+                            YT::to_float((uint16_t)(u.y & 0xffffu)), YT::to_float((uint16_t)(u.y >> 16))};
+#pragma unroll
+        for (int r = 0; r < 4; ++r) {
+          const float d = __builtin_fmaf(nsg, acc[i][j][q * 4 + r], y[r]);
+          sumsq += d * d;
+        }
+      }
+    part += a.token_w[t] * sumsq;
+    sq[j] = sumsq;
+  }
+}
+
 // ---------------------------------------------------------------------------
 // Tile epilogue shared by both kernels.  Accumulator layout of a 32x32
 // fragment: lane holds column (lane%32) and rows 8*(v/4) + 4*(lane/32) + v%4,
@@ -153,7 +208,7 @@ __device__ __forceinline__ void loss_rows(const GemmDev& a, f32x16 (&acc)[FA][FB
 // output rows [wo*WO, +WO) and tokens [wt*WT, +WT) of the tile at (o0, t0).
 // `red` holds one float per wave, `rows` NWO x BT floats (per-token row sums;
 // only used by EPI_LOSS_TOK).  Every wave of the block must call this.
-template <int EPI, int FA, int FB, int NWO, int NWT, int BT>
+template <int EPI, int FA, int FB, int NWO, int NWT, int BT, bool YLDS = false>
 __device__ __forceinline__ void tile_epilogue(const GemmDev& a, f32x16 (&acc)[FA][FB], int cand, int to,
                                               int tt, int64_t o0, int64_t t0, int wo, int wt,
                                               float* red, float* rows) {
@@ -187,6 +242,11 @@ __device__ __forceinline__ void tile_epilogue(const GemmDev& a, f32x16 (&acc)[FA
   float part = 0.0f;
   float sq[FB];
   const bool interior = (o0 + NWO * WO <= a.c_out) && (t0 + BT <= a.n_tok);
+  if (YLDS && EPI == EPI_LOSS && interior && a.ydt != TLQ_F32) {
+    unsigned char* ylds = reinterpret_cast<unsigned char*>(rows) + wave * (WO * WT * 2);
+    if (a.ydt == TLQ_F16) loss_rows_lds<F16, FA, FB>(a, acc, tsc, o0 + wo * WO, t0 + wt * WT, sq, part, ylds);
+    else loss_rows_lds<BF16, FA, FB>(a, acc, tsc, o0 + wo * WO, t0 + wt * WT, sq, part, ylds);
+  } else
   if (interior && a.ydt == TLQ_F16) loss_rows<TLQ_F16, true, FA, FB>(a, acc, tsc, o0 + wo * WO, t0 + wt * WT, sq, part);
   else if (interior && a.ydt == TLQ_F32) loss_rows<TLQ_F32, true, FA, FB>(a, acc, tsc, o0 + wo * WO, t0 + wt * WT, sq, part);
   else if (interior) loss_rows<TLQ_BF16, true, FA, FB>(a, acc, tsc, o0 + wo * WO, t0 + wt * WT, sq, part);
@@ -591,8 +651,8 @@ __global__ __launch_bounds__(NWO * NWT * 64) void gemm_dma_kernel(GemmDev a) {
 
   // every LDS-DMA write has landed and every wave is past its last fragment read:
   // the tile memory is free for the per-token row sums
-  tile_epilogue<EPI, FA, FB, NWO, NWT, BT>(a, acc, cand, to, tt, o0, t0, wo, wt, red,
-                                           reinterpret_cast<float*>(lds));
+  tile_epilogue<EPI, FA, FB, NWO, NWT, BT, (NSTAGE * STAGE >= NW * WO * WT * 2) && FA == 4>(
+      a, acc, cand, to, tt, o0, t0, wo, wt, red, reinterpret_cast<float*>(lds));
 #endif
 }
 
