@@ -165,7 +165,14 @@ tlq_status tlq_weighted_layer_err(const void* X, int64_t n_tok, int64_t c_in, in
  * alpha_grid: float [n_alpha], 1 <= n_alpha <= TLQ_MAX_ALPHA.
  * Outputs: best_scales float [c_in] (= s_table[best_idx]); best_idx int32 [1]
  * (first minimum; -1 if no candidate has a finite loss); losses float
- * [n_alpha] (+inf where not finite); s_table_out float [n_alpha, c_in] or NULL. */
+ * [n_alpha] (+inf where not finite); s_table_out float [n_alpha, c_in] or NULL.
+ * Arithmetic: 16-bit matrix-core operands, float accumulation.  Without
+ * activation quantisation the operand is the folded weight
+ * round16(deq_k / s_k); from 6 weight bits on, and for problems smaller than
+ * 256 x 256 outputs, it is the difference round16(deq_k / s_k - W) and the
+ * residual is formed against Y_ref - X W^T kept in float (one more
+ * contraction and n_tok x c_out floats of workspace), because there the
+ * rounding of the folded weight itself would show in the loss. */
 size_t tlq_scale_search_workspace_bytes(int64_t n_tok, int64_t c_in, int64_t c_out,
                                         int32_t n_alpha, const tlq_params* p);
 tlq_status tlq_scale_search(const void* X, int64_t n_tok, int64_t c_in, int64_t ldx,

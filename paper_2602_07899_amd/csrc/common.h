@@ -92,6 +92,8 @@ struct QuantArgs {
   void* what; int64_t what_cand_stride;  // elements between candidates
   bool what_f16;          // round `what` to fp16 even when W is bf16
   uint8_t* codes; uint8_t* zp; float* delta; void* wdq; int64_t ld_dq;
+  // difference form: `what` receives deq*inv - W*2^shift (shift from xmax_bits, 0 when NULL)
+  bool diff; const uint32_t* xmax_bits;
 };
 hipError_t launch_fake_quant(const QuantArgs& a, hipStream_t stream);
 
@@ -125,6 +127,10 @@ struct GemmArgs {
 void gemm_tile_counts(int64_t n_tok, int64_t c_out, int64_t* tiles_o, int64_t* tiles_t);
 hipError_t launch_gemm_loss(const GemmArgs& a, hipStream_t stream);
 hipError_t launch_gemm_store(const GemmArgs& a, hipStream_t stream);
+
+// D[t,o] = Y[t,o] - D[t,o] (D float, row stride ldd)
+hipError_t launch_sub_from_y(const void* Y, int64_t ldy, int ydt, float* D, int64_t ldd, int64_t n_tok,
+                             int64_t c_out, hipStream_t stream);
 
 // S4 final combine + S5 selection.
 hipError_t launch_finalize(const float* partial, int n_cand, int64_t tiles_per_cand, int64_t c_out,

@@ -21,6 +21,7 @@ struct QuantDev {
   const float* s_table; const float* inv_table; int n_cand;
   uint16_t* what; int64_t what_cand_stride; bool what_f16;
   uint8_t* codes; uint8_t* zp; float* delta; uint16_t* wdq; int64_t ld_dq;
+  bool diff; const uint32_t* xmax_bits;  // what = deq*inv - W*2^shift
 };
 
 template <bool SYM>
@@ -94,6 +95,7 @@ __global__ __launch_bounds__(256) void quant_pow2_kernel(QuantDev a) {
   }
   const int64_t gidx = row * (a.c_in / a.group) + c / a.group;
 
+  const float wsub = a.diff ? (a.xmax_bits ? __builtin_ldexpf(1.0f, shift_from_bf16_bits(*a.xmax_bits)) : 1.0f) : 0.0f;
   for (int k = 0; k < a.n_cand; ++k) {
     float s[8], inv[8];
 #pragma unroll
@@ -137,7 +139,8 @@ __global__ __launch_bounds__(256) void quant_pow2_kernel(QuantDev a) {
     for (int j = 0; j < 8; ++j) {
       float code, deq;
       quant_one<SYM>(ws[j], delta, rdelta, zpf, a, code, deq);
-      const float folded = deq * inv[j];
+      float folded = deq * inv[j];
+      if (a.diff) folded -= w[j] * wsub;
       hw[j >> 1] |= (uint32_t)(a.what_f16 ? F16::from_float(folded) : T::from_float(folded)) << ((j & 1) * 16);
       if (AUX) {
         cw[j >> 2] |= ((uint32_t)code & 0xffu) << ((j & 3) * 8);
@@ -170,6 +173,7 @@ __global__ __launch_bounds__(256) void quant_any_kernel(QuantDev a) {
   if (wave >= a.c_out * G) return;
   const int64_t row = wave / G;
   const int64_t c0 = (wave % G) * a.group;
+  const float wsub = a.diff ? (a.xmax_bits ? __builtin_ldexpf(1.0f, shift_from_bf16_bits(*a.xmax_bits)) : 1.0f) : 0.0f;
   for (int k = 0; k < a.n_cand; ++k) {
     const float* sk = a.s_table ? a.s_table + (int64_t)k * a.c_in : nullptr;
     const float* ik = (a.inv_table && a.what) ? a.inv_table + (int64_t)k * a.c_in : nullptr;
@@ -192,7 +196,8 @@ __global__ __launch_bounds__(256) void quant_any_kernel(QuantDev a) {
       quant_one<SYM>(ws, delta, rdelta, zpf, a, code, deq);
       if (a.what)
         {
-          const float folded = deq * (ik ? ik[c] : 1.0f);
+          float folded = deq * (ik ? ik[c] : 1.0f);
+          if (a.diff) folded -= T::to_float(a.W[row * a.ldw + c]) * wsub;
           a.what[(int64_t)k * a.what_cand_stride + row * a.c_in + c] =
               a.what_f16 ? F16::from_float(folded) : T::from_float(folded);
         }
@@ -344,6 +349,7 @@ hipError_t launch_fake_quant(const QuantArgs& q, hipStream_t stream) {
   d.s_table = q.s_table; d.inv_table = q.inv_table; d.n_cand = q.n_cand;
   d.what = (uint16_t*)q.what; d.what_cand_stride = q.what_cand_stride; d.what_f16 = q.what_f16;
   d.codes = q.codes; d.zp = q.zp; d.delta = q.delta; d.wdq = (uint16_t*)q.wdq; d.ld_dq = q.ld_dq;
+  d.diff = q.diff; d.xmax_bits = q.xmax_bits;
   const bool pow2 = d.group >= 8 && d.group <= 512 && (d.group & (d.group - 1)) == 0;
   const double bytes = (double)q.c_out * (double)q.c_in * (2.0 + 2.0 * (q.what ? q.n_cand : 0) +
                                                            (q.codes ? 1.0 : 0.0) + (q.wdq ? 2.0 : 0.0));

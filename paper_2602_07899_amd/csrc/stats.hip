@@ -273,4 +273,28 @@ hipError_t launch_token_err_reduce(const float* tok_partial, int64_t tiles_o, in
   return hipGetLastError();
 }
 
+// D[t,o] = Y[t,o] - D[t,o]; one thread per element (used once per search in the difference form)
+__global__ __launch_bounds__(256) void sub_from_y_kernel(const void* __restrict__ Y, int64_t ldy, int ydt,
+                                                         float* __restrict__ D, int64_t ldd, int64_t n_tok,
+                                                         int64_t c_out) {
+  const int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x;
+  if (i >= n_tok * c_out) return;
+  const int64_t t = i / c_out, o = i % c_out;
+  float y;
+  if (ydt == TLQ_F32) y = ((const float*)Y)[t * ldy + o];
+  else {
+    const uint16_t b = ((const uint16_t*)Y)[t * ldy + o];
+    y = ydt == TLQ_F16 ? F16::to_float(b) : BF16::to_float(b);
+  }
+  D[t * ldd + o] = y - D[t * ldd + o];
+}
+
+hipError_t launch_sub_from_y(const void* Y, int64_t ldy, int ydt, float* D, int64_t ldd, int64_t n_tok,
+                             int64_t c_out, hipStream_t stream) {
+  ProfScope ps("sub_from_y", stream, (double)n_tok * (double)c_out * 10.0);
+  sub_from_y_kernel<<<(unsigned)ceil_div(n_tok * c_out, 256), 256, 0, stream>>>(Y, ldy, ydt, D, ldd, n_tok, c_out);
+  return hipGetLastError();
+}
+
 }  // namespace tlq
+
