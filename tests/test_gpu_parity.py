@@ -380,13 +380,14 @@ def test_apply_best(gpu, n, ci, co, bits, bf16):
 
 
 # --------------------------------------- full size, the benchmark's launch shape
-def test_full_size_7b_linear_sampled_parity(gpu):
-    """o_proj-shaped linear of the 7B workload (10240 tokens, 4096x4096, 20
-    candidates), exactly as the benchmark launches it.  The oracle evaluates
-    three candidates in full and 64 sampled tokens for every candidate."""
+@pytest.mark.parametrize("li", [3, 4, 6])
+def test_full_size_7b_linear_sampled_parity(gpu, li):
+    """o_proj (4096x4096), gate_proj (11008x4096: 43 tile rows, ragged patches) and down_proj
+    (4096x11008: two token chunks) of the 7B workload (10240 tokens, 20 candidates), exactly as
+    the benchmark launches them.  The oracle evaluates three candidates in full and 64 sampled
+    tokens for every third candidate."""
     import torch
     c = wl.CONFIGS["cfg2_7b_w4"]
-    li = 3
     X, W, w = wl.make_tokens(c, li), wl.make_weight(c, li), wl.make_token_weights(c, li)
     Y = orc.ref_output(X, W).astype(np.float16)
     al = wl.alpha_grid(c.n_alpha)
@@ -395,7 +396,7 @@ def test_full_size_7b_linear_sampled_parity(gpu):
     ost = orc.scale_table(orc.x_stat_mean(X), al)      # the oracle's own table feeds the oracle
     ulp = np.abs(st.view(np.int32).astype(np.int64) - ost.view(np.int32))
     assert ulp.max() <= 1
-    print(f"7B o_proj: {int((ulp > 0).sum())} scale-table entries off by one ulp; best alpha index {idx}")
+    print(f"7B {c.linears[li].name}: {int((ulp > 0).sum())} scale-table entries off by one ulp; best alpha index {idx}")
     # (a) full oracle on three candidates, including the selected one
     for k in sorted({0, idx, 19}):
         _, _, _, deq = orc.fake_quant(W, ost[k], c.bits, c.group)
