@@ -201,6 +201,41 @@ __device__ __forceinline__ void loss_rows_lds(const GemmDev& a, f32x16 (&acc)[FA
   }
 }
 
+// Store epilogue of an interior wave tile with a 16-bit output, through LDS: every lane drops
+// its rounded values into `ylds` (WT x WO 16-bit, this wave's own, same chunk-XOR-token layout
+// as loss_rows_lds), then the wave writes whole 128-byte lines, 8 lines per instruction.
+// Storing straight from the accumulator layout writes 8-byte pieces of 32 lines per instruction.
+template <typename YT, int FA, int FB>
+__device__ __forceinline__ void store_rows_lds(const GemmDev& a, f32x16 (&acc)[FA][FB], const float* tsc,
+                                               int64_t ow, int64_t tw, unsigned char* ylds) {
+  constexpr int WO = FA * 32, WT = FB * 32;
+  constexpr int CPR = WO / 8, RPI = 64 / CPR;
+  static_assert(CPR == 16 && WT % RPI == 0, "copy shape");
+  const int lane = threadIdx.x & 63, frow = lane & 31, fhi = lane >> 5;
+#pragma unroll
+  for (int j = 0; j < FB; ++j) {
+    const int tok = j * 32 + frow;
+    const float sg = tsc ? tsc[tw + tok] : 1.0f;
+#pragma unroll
+    for (int i = 0; i < FA; ++i)
+#pragma unroll
+      for (int q = 0; q < 4; ++q) {
+        uint2 u;
+        u.x = (uint32_t)YT::from_float(sg * acc[i][j][q * 4]) | ((uint32_t)YT::from_float(sg * acc[i][j][q * 4 + 1]) << 16);
+        u.y = (uint32_t)YT::from_float(sg * acc[i][j][q * 4 + 2]) | ((uint32_t)YT::from_float(sg * acc[i][j][q * 4 + 3]) << 16);
+        *reinterpret_cast<uint2*>(ylds + tok * (WO * 2) + (((i * 4 + q) ^ (tok & 15)) << 4) + fhi * 8) = u;
+      }
+  }
+  uint16_t* Y = (uint16_t*)a.Yout;
+  const int cr = lane / CPR, cc = lane % CPR;
+#pragma unroll
+  for (int j = 0; j < WT / RPI; ++j) {
+    const int row = j * RPI + cr;
+    const uint4 v = *reinterpret_cast<const uint4*>(ylds + row * (WO * 2) + ((cc ^ (row & 15)) << 4));
+    *reinterpret_cast<uint4*>(Y + (tw + row) * a.ldo + ow + cc * 8) = v;
+  }
+}
+
 // ---------------------------------------------------------------------------
 // Tile epilogue shared by both kernels.  Accumulator layout of a 32x32
 // fragment: lane holds column (lane%32) and rows 8*(v/4) + 4*(lane/32) + v%4,
@@ -217,6 +252,13 @@ __device__ __forceinline__ void tile_epilogue(const GemmDev& a, f32x16 (&acc)[FA
   const int frow = lane & 31, fhi = lane >> 5;
   const float* tsc = a.tok_scale ? a.tok_scale + (int64_t)cand * a.n_tok : nullptr;
   if (EPI == EPI_STORE) {
+    if (YLDS && a.odt != TLQ_F32 && (o0 + NWO * WO <= a.c_out) && (t0 + BT <= a.n_tok) && (a.ldo % 8) == 0 &&
+        ((uintptr_t)a.Yout % 16) == 0) {
+      unsigned char* ylds = reinterpret_cast<unsigned char*>(rows) + wave * (WO * WT * 2);
+      if (a.odt == TLQ_F16) store_rows_lds<F16, FA, FB>(a, acc, tsc, o0 + wo * WO, t0 + wt * WT, ylds);
+      else store_rows_lds<BF16, FA, FB>(a, acc, tsc, o0 + wo * WO, t0 + wt * WT, ylds);
+      return;
+    }
 #pragma unroll
     for (int j = 0; j < FB; ++j) {
       const int64_t t = t0 + wt * WT + j * 32 + frow;
