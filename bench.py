@@ -26,7 +26,7 @@ PEAK_FP16_TFLOPS = 2500.0      # MI355X dense fp16 MFMA peak (published)
 # Bytes per gemm_loss launch that cross the L2/fabric boundary, from two rocprofv3 --pmc
 # runs of this file (FETCH_SIZE, WRITE_SIZE), each scaled by what the same counter reads
 # for the known-size calibration copy below (x1.999 and x1.000); summary under profiles/.
-MEASURED_TRAFFIC_BYTES_PER_LAUNCH = 2.066e10
+MEASURED_TRAFFIC_BYTES_PER_LAUNCH = 1.998e10
 
 
 def cpu_baseline(wl, orc, workload):
