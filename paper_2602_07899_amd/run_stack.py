@@ -106,6 +106,7 @@ def run(stack_name, bits, mode="passact2", joint=False, n_layers=None, n_samples
         "evals_per_s": (7 * layers * sw.n_alpha) / wall,
         "gemm_loss_tflops": (gl.total_work / (gl.total_ms * 1e-3) / 1e12) if gl and gl.total_ms > 0 else None,
         "kernels": {n: {"launches": k.launches, "ms": round(k.total_ms, 3)} for n, k in prof.items()},
+        "peak_hbm_bytes": int(torch.cuda.max_memory_allocated()),
         "h_finite": bool(torch.isfinite(hq.float()).all().item()),
         "h_rms": float(hq.float().pow(2).mean().sqrt().item()),
         "stream_gap_rel": float(((hq.float() - hf.float()).norm() / hf.float().norm()).item()),
