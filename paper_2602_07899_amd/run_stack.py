@@ -56,7 +56,7 @@ def device_weights(sw, dev, dtype):
 
 
 def run(stack_name, bits, mode="passact2", joint=False, n_layers=None, n_samples=None, journal_path=None,
-        act_bits=0, log=print):
+        act_bits=0, log=print, group=None, symmetric=False):
     import torch
     if not torch.cuda.is_available():
         raise RuntimeError("run_stack needs a GPU")
@@ -65,7 +65,8 @@ def run(stack_name, bits, mode="passact2", joint=False, n_layers=None, n_samples
     bf16 = sw.act_dtype == "bf16"
     dtype = torch.bfloat16 if bf16 else torch.float16
     code = tlq.BF16 if bf16 else tlq.F16
-    p = tlq.params(bits=bits, group=sw.group, x_dtype=code, yref_dtype=code, act_bits=act_bits)
+    p = tlq.params(bits=bits, group=sw.group if group is None else group, symmetric=1 if symmetric else 0,
+                   x_dtype=code, yref_dtype=code, act_bits=act_bits)
     layers = n_layers or sw.n_layers
     h0, w = device_inputs(sw, dev, dtype, n_samples)
     al = torch.from_numpy(wl.alpha_grid(sw.n_alpha)).to(dev)
@@ -94,15 +95,15 @@ def run(stack_name, bits, mode="passact2", joint=False, n_layers=None, n_samples
     block_ms = sum(k.total_ms for n, k in prof.items() if n in BLOCK_KERNELS)
     prop_ms = sum(k.total_ms for n, k in prof.items() if n not in SEARCH_KERNELS and n not in BLOCK_KERNELS)
     gl = prof.get("gemm_loss")
-    n_search = gl.launches if gl else 0
     out = {
-        "stack": stack_name, "bits": bits, "mode": mode, "joint": joint, "act_bits": act_bits, "layers": layers,
+        "stack": stack_name, "bits": bits, "group": p.group, "symmetric": bool(p.symmetric), "mode": mode,
+        "joint": joint, "act_bits": act_bits, "layers": layers,
         "n_tok": int(h0.shape[0]), "hidden": sw.hidden, "ffn": sw.ffn, "dtype": sw.act_dtype,
         # search = S0..S5; propagate = full-precision targets and the quantised outputs fed forward (S6);
         # block = the decoder block between the linears; the rest is weight generation and host time
         "wall_s": wall, "search_kernels_s": search_ms / 1e3, "propagate_kernels_s": prop_ms / 1e3,
         "block_kernels_s": block_ms / 1e3, "other_s": wall - (search_ms + prop_ms + block_ms) / 1e3,
-        "evals": n_search * sw.n_alpha if not joint else None,
+        "evals": 7 * layers * sw.n_alpha,
         "evals_per_s": (7 * layers * sw.n_alpha) / wall,
         "gemm_loss_tflops": (gl.total_work / (gl.total_ms * 1e-3) / 1e12) if gl and gl.total_ms > 0 else None,
         "kernels": {n: {"launches": k.launches, "ms": round(k.total_ms, 3)} for n, k in prof.items()},
@@ -124,10 +125,13 @@ def main():
     ap.add_argument("--layers", type=int, default=None)
     ap.add_argument("--samples", type=int, default=None)
     ap.add_argument("--act-bits", type=int, default=0)
+    ap.add_argument("--group", type=int, default=None, help="quantisation group (0 = whole row); default: the stack's")
+    ap.add_argument("--symmetric", action="store_true")
     ap.add_argument("--journal", default=None)
     ap.add_argument("--brief", action="store_true", help="leave the per-block records out of the summary")
     a = ap.parse_args()
-    out = run(a.stack, a.bits, a.mode, a.joint, a.layers, a.samples, a.journal, a.act_bits)
+    out = run(a.stack, a.bits, a.mode, a.joint, a.layers, a.samples, a.journal, a.act_bits, group=a.group,
+              symmetric=a.symmetric)
     if a.brief:
         out.pop("blocks")
     print(json.dumps(out))
