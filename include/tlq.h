@@ -150,7 +150,10 @@ tlq_status tlq_act_fake_quant(const void* X, int64_t n_tok, int64_t c_in, int64_
  *   loss   = sum_t token_w[t] * err[t]
  * X [n_tok,c_in], Wdq [c_out,c_in]: x_dtype; inv_s: float [c_in] or NULL (ones);
  * Y_ref [n_tok,c_out] yref_dtype; token_w float [n_tok] (used as given).
- * loss: out float [1]; per_token_err: out float [n_tok] or NULL. */
+ * loss: out float [1]; per_token_err: out float [n_tok] or NULL.
+ * The operand that enters the matrix cores is round16(Wdq * inv_s); on problems with only a
+ * handful of outputs that rounding can show in the loss beyond 1e-3 (tlq_scale_search, which
+ * also sees W, avoids it there). */
 size_t tlq_weighted_layer_err_workspace_bytes(int64_t n_tok, int64_t c_in, int64_t c_out,
                                               const tlq_params* p);
 tlq_status tlq_weighted_layer_err(const void* X, int64_t n_tok, int64_t c_in, int64_t ldx,

@@ -48,6 +48,10 @@ Parity pins (see tests/test_oracle_pins.py): brute force on tiny layers
 alpha=1 closed forms, uniform-weight MSE, smoothing identity with an identity
 quantiser, grid idempotence, Delta^2/12 error energy (Sec. 2.2), power-of-two
 scale invariance, max-code closed form for the symmetric variant.
+Every function of this module has at least one such pin.  Not pinned, and not
+pinnable here: that these definitions reproduce the paper's downstream accuracy
+tables - that needs the trained models and evaluation suites (parity unpinned
+for accuracy).
 """
 from __future__ import annotations
 
