@@ -117,17 +117,22 @@ def _gpu_run(gpu, sw, h0, tW, w, al, bits, mode, joint, journal=None, keep=True,
                             sw.seq_len, mode=mode, joint=joint, journal=journal, keep=keep)
 
 
-@pytest.mark.parametrize("mode,joint", [("passact2", False), ("passact1", False), ("none", False),
-                                        ("passact2", True), ("passact1", True)])
-def test_stack_teacher_forced_parity(gpu, mode, joint):
+# setting = (bits, group, symmetric, act_bits); the last one is the paper's own (W4 per-channel symmetric, A8)
+@pytest.mark.parametrize("mode,joint,setting", [
+    ("passact2", False, (4, 128, False, 0)), ("passact1", False, (4, 128, False, 0)), ("none", False, (4, 128, False, 0)),
+    ("passact2", True, (4, 128, False, 0)), ("passact1", True, (4, 128, False, 0)),
+    ("passact2", False, (4, 0, True, 8)), ("passact2", True, (3, 0, True, 6)), ("passact1", False, (8, 128, False, 0))])
+def test_stack_teacher_forced_parity(gpu, mode, joint, setting):
     """Every search of the oracle's stack run is repeated on the GPU with the ORACLE's
     exposed input and target (so an upstream one-ulp difference cannot hide or fake a
     mismatch), then the glue after it is checked on the oracle's tensors."""
     import torch
     sw, h0, Ws, w, al, tW = _mini(gpu)
-    bits = 4
-    recs = ost.run_stack(h0, Ws, w, bits, sw.group, al, sw.n_heads, sw.seq_len, BF, mode=mode, joint=joint)
-    p = tlq.params(bits=bits, group=sw.group, x_dtype=tlq.BF16, yref_dtype=tlq.BF16)
+    bits, group, sym, abits = setting
+    recs = ost.run_stack(h0, Ws, w, bits, group, al, sw.n_heads, sw.seq_len, BF, mode=mode, joint=joint,
+                         symmetric=sym, act_bits=abits)
+    p = tlq.params(bits=bits, group=group, symmetric=1 if sym else 0, act_bits=abits, x_dtype=tlq.BF16,
+                   yref_dtype=tlq.BF16)
     tw, tal = torch.from_numpy(w).to(gpu), torch.from_numpy(al).to(gpu)
     for l, layer in enumerate(recs):
         for names in gstack.GROUPS:
