@@ -63,7 +63,7 @@ def silu_mul(g, u):
         return g / (1.0 + np.exp(-g)) * u
 
 
-def _search_group(Xq, Xfp, Ws, token_w, bits, group, alphas, joint, rnd, kw):
+def _search_group(Xq, Xfp, Ws, token_w, bits, group, alphas, joint, rnd, kw, x_stat=None):
     """Search the linears `Ws` that share the exposed input Xq; the target is
     computed from Xfp (== Xq unless two streams are kept).  Returns per-linear
     records and the quantised / full-precision outputs."""
@@ -71,10 +71,10 @@ def _search_group(Xq, Xfp, Ws, token_w, bits, group, alphas, joint, rnd, kw):
     Ys = [rnd(orc.ref_output(Xfp, W)) for W in Ws]
     if joint and len(Ws) > 1:
         Wc, Yc = np.concatenate(Ws, axis=0), np.concatenate(Ys, axis=1)
-        res = orc.scale_search(Xq, Wc, Yc, token_w, bits, group, alphas, **kw)
+        res = orc.scale_search(Xq, Wc, Yc, token_w, bits, group, alphas, x_stat=x_stat, **kw)
         results = [res] * len(Ws)
     else:
-        results = [orc.scale_search(Xq, W, Y, token_w, bits, group, alphas, **kw) for W, Y in zip(Ws, Ys)]
+        results = [orc.scale_search(Xq, W, Y, token_w, bits, group, alphas, x_stat=x_stat, **kw) for W, Y in zip(Ws, Ys)]
     for W, Y, res in zip(Ws, Ys, results):
         with np.errstate(over="ignore"):
             Zq.append(rnd(orc.apply_best(Xq, W, res["best_scales"], bits, group, **kw)))
@@ -84,10 +84,12 @@ def _search_group(Xq, Xfp, Ws, token_w, bits, group, alphas, joint, rnd, kw):
 
 
 def run_stack(h0, layer_weights, token_w, bits, group, alphas, n_heads, seq_len, rnd,
-              mode="passact2", joint=False, symmetric=False, act_bits=0):
+              mode="passact2", joint=False, symmetric=False, act_bits=0, xstat_fn=None):
     """h0 [n_tok, d] (already in the activation type); layer_weights: one list of
     7 weight matrices per decoder block, in LINEARS order; rnd(a) rounds a float64
     array to the activation type (returned as an array numpy can compute with).
+    xstat_fn(layer, names, X) may supply the per-channel statistic of a group's exposed
+    input (e.g. the gradient-guided Top-K maximum of Sec. 3.1.2); None = mean |x|.
     Returns records[layer][linear] with the exposed input X, the target Y_ref, the
     search result and the quantised output Z."""
     assert mode in ("none", "passact1", "passact2")
@@ -96,12 +98,13 @@ def run_stack(h0, layer_weights, token_w, bits, group, alphas, n_heads, seq_len,
     hq = np.asarray(h0)
     hf = hq
     out = []
-    for Ws in layer_weights:
+    for layer, Ws in enumerate(layer_weights):
         recs = {}
 
         def block(xq, xf, names):
             idx = [LINEARS.index(n) for n in names]
-            r, zq, zf = _search_group(xq, xf, [Ws[i] for i in idx], token_w, bits, group, alphas, joint, rnd, kw)
+            xs = xstat_fn(layer, names, xq) if xstat_fn is not None else None
+            r, zq, zf = _search_group(xq, xf, [Ws[i] for i in idx], token_w, bits, group, alphas, joint, rnd, kw, xs)
             for n, rec in zip(names, r):
                 recs[n] = rec
             if mode == "none":              # the quantised outputs are never fed forward

@@ -25,6 +25,7 @@ from . import workloads as wl
 SEARCH_KERNELS = ("xstat_partial", "xstat_final", "scale_table", "fake_quant", "gemm_loss", "finalize", "bf16_to_f16",
                   "act_quant")
 BLOCK_KERNELS = ("rmsnorm_mul", "causal_attention", "silu_mul", "residual_add")
+SELECT_KERNELS = ("token_importance", "topk_mask")
 
 
 def device_inputs(sw, dev, dtype, n_samples=None):
@@ -55,8 +56,33 @@ def device_weights(sw, dev, dtype):
     return fn
 
 
+def topk_xstat_fn(sw, n_samples, p, dev, dtype, frac=0.5):
+    """x_stat = max over the Top-(frac) positions by accumulated gradient norm (Sec. 3.1.2).  The
+    gradients are synthetic stand-ins (they need the trained model and its loss): N(0,1) scaled
+    per position so that most visual positions carry almost no gradient."""
+    import torch
+    per = sw.seq_len
+    g = torch.Generator(device=dev)
+    amp = torch.cat([torch.exp(torch.randn(sw.n_vis, generator=g.manual_seed(sw.seed * 1000 + 777), device=dev) * 1.5 - 4.0),
+                     torch.exp(torch.randn(sw.n_txt, generator=g, device=dev) * 0.5)])
+
+    def fn(layer, names, X):
+        c = X.shape[1]
+        g.manual_seed((sw.seed * 1000 + layer) * 16 + len(names) + (3 if c != sw.hidden else 0))
+        G = (torch.randn((n_samples * per, c), generator=g, device=dev, dtype=torch.float32)
+             * amp.repeat(n_samples)[:, None]).to(dtype)
+        sum_n = torch.empty(per, dtype=torch.float64, device=dev)
+        tlq.token_importance(G, n_samples, p, sum_n)
+        mask = torch.empty(per, dtype=torch.uint8, device=dev)
+        tlq.topk_mask(sum_n, max(1, int(per * frac)), mask)
+        xs = torch.empty(c, dtype=torch.float32, device=dev)
+        tlq.x_stat_masked(X, mask, p, xs)
+        return xs
+    return fn
+
+
 def run(stack_name, bits, mode="passact2", joint=False, n_layers=None, n_samples=None, journal_path=None,
-        act_bits=0, log=print, group=None, symmetric=False):
+        act_bits=0, log=print, group=None, symmetric=False, xstat="mean"):
     import torch
     if not torch.cuda.is_available():
         raise RuntimeError("run_stack needs a GPU")
@@ -85,19 +111,21 @@ def run(stack_name, bits, mode="passact2", joint=False, n_layers=None, n_samples
         log(f"[run_stack] W{bits} {mode} block {layer + 1}/{layers} done at {time.time() - t0:7.2f} s  best_idx={idx}")
         sys.stdout.flush()
 
+    xfn = topk_xstat_fn(sw, n_samples or sw.n_samples, p, dev, dtype) if xstat == "topk" else None
     _, hq, hf = gstack.run_stack(h0, device_weights(sw, dev, dtype), layers, w, al, p, sw.n_heads, sw.seq_len,
-                                 mode=mode, joint=joint, journal=journal, on_layer=on_layer)
+                                 mode=mode, joint=joint, journal=journal, on_layer=on_layer, xstat_fn=xfn)
     torch.cuda.synchronize()
     wall = time.time() - t0
     tlq.profile_enable(False)
     prof = {k.name: k for k in tlq.profile_read()}
-    search_ms = sum(k.total_ms for n, k in prof.items() if n in SEARCH_KERNELS)
+    search_ms = sum(k.total_ms for n, k in prof.items() if n in SEARCH_KERNELS or n in SELECT_KERNELS)
     block_ms = sum(k.total_ms for n, k in prof.items() if n in BLOCK_KERNELS)
-    prop_ms = sum(k.total_ms for n, k in prof.items() if n not in SEARCH_KERNELS and n not in BLOCK_KERNELS)
+    prop_ms = sum(k.total_ms for n, k in prof.items()
+                  if n not in SEARCH_KERNELS and n not in BLOCK_KERNELS and n not in SELECT_KERNELS)
     gl = prof.get("gemm_loss")
     out = {
         "stack": stack_name, "bits": bits, "group": p.group, "symmetric": bool(p.symmetric), "mode": mode,
-        "joint": joint, "act_bits": act_bits, "layers": layers,
+        "joint": joint, "act_bits": act_bits, "x_stat": xstat, "layers": layers,
         "n_tok": int(h0.shape[0]), "hidden": sw.hidden, "ffn": sw.ffn, "dtype": sw.act_dtype,
         # search = S0..S5; propagate = full-precision targets and the quantised outputs fed forward (S6);
         # block = the decoder block between the linears; the rest is weight generation and host time
@@ -127,11 +155,13 @@ def main():
     ap.add_argument("--act-bits", type=int, default=0)
     ap.add_argument("--group", type=int, default=None, help="quantisation group (0 = whole row); default: the stack's")
     ap.add_argument("--symmetric", action="store_true")
+    ap.add_argument("--xstat", default="mean", choices=("mean", "topk"),
+                    help="mean |x| (default) or the maximum over the Top-50%% positions by synthetic gradient norm")
     ap.add_argument("--journal", default=None)
     ap.add_argument("--brief", action="store_true", help="leave the per-block records out of the summary")
     a = ap.parse_args()
     out = run(a.stack, a.bits, a.mode, a.joint, a.layers, a.samples, a.journal, a.act_bits, group=a.group,
-              symmetric=a.symmetric)
+              symmetric=a.symmetric, xstat=a.xstat)
     if a.brief:
         out.pop("blocks")
     print(json.dumps(out))

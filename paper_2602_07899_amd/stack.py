@@ -65,13 +65,16 @@ class Journal:
 
 
 def run_stack(h0, weights_fn, n_layers, token_w, alpha_grid, p, n_heads, seq_len, mode="passact2",
-              joint=False, journal=None, keep=False, on_layer=None):
+              joint=False, journal=None, keep=False, on_layer=None, xstat_fn=None):
     """h0 [n_tok, n_heads*128] device tensor in the activation type; weights_fn(layer)
     returns the 7 device weight matrices of one block (LINEARS order).  Returns
     (records, h_q, h_fp): records[layer][linear] holds device tensors best_idx, losses,
     best_scales (plus X, Y_ref, Z when keep=True); h_q / h_fp are the final hidden
     states of the quantised / full-precision streams (the same tensor unless
-    mode == "passact1")."""
+    mode == "passact1").  xstat_fn(layer, names, X) may return a device float vector with the
+    per-channel statistic of a group's exposed input (e.g. the gradient-guided Top-K maximum,
+    Sec. 3.1.2, built with tlq.token_importance / topk_mask / x_stat_masked); None = the
+    statistic p.xstat_kind names."""
     import torch
     assert mode in ("none", "passact1", "passact2")
     dev, act = h0.device, h0.dtype
@@ -104,6 +107,7 @@ def run_stack(h0, weights_fn, n_layers, token_w, alpha_grid, p, n_heads, seq_len
         for W, Yi in zip(Ws, Ys):
             tlq.ref_output(Xfp, W, Yi, p)
         Z = None if mode == "none" else new(tot)
+        xs_in = xstat_fn(layer, names, Xq) if xstat_fn is not None else None
         units = [(names, torch.cat(Ws, dim=0) if len(Ws) > 1 else Ws[0], Y, Z)] if joint else \
                 [((n,), W, Yi, None if Z is None else Z[:, o:o + w]) for n, W, Yi, o, w in zip(names, Ws, Ys, offs, widths)]
         for unames, W, Yu, Zu in units:
@@ -113,13 +117,16 @@ def run_stack(h0, weights_fn, n_layers, token_w, alpha_grid, p, n_heads, seq_len
             losses = torch.empty(na, dtype=torch.float32, device=dev)
             old = journal.get(layer, unames[0]) if journal is not None else None
             if old is not None:                                   # resume: rebuild the chosen scales
-                xs = torch.empty(c_in, dtype=torch.float32, device=dev)
-                tlq.x_stat(Xq, p, xs, workspace=ws)
+                xs = xs_in
+                if xs is None:
+                    xs = torch.empty(c_in, dtype=torch.float32, device=dev)
+                    tlq.x_stat(Xq, p, xs, workspace=ws)
                 tlq.scale_table(xs, alpha_grid[old["best_idx"]:old["best_idx"] + 1], best)
                 idx.fill_(old["best_idx"])
                 losses.copy_(torch.tensor(old["losses"], dtype=torch.float32))
             else:
-                tlq.scale_search(Xq, W, Yu, token_w, alpha_grid, p, best, idx, losses, workspace=ws)
+                tlq.scale_search(Xq, W, Yu, token_w, alpha_grid, p, best, idx, losses, x_stat_in=xs_in,
+                                 workspace=ws)
                 if journal is not None:
                     li, ll = int(idx.item()), [float(v) for v in losses.tolist()]
                     for n in unames:
