@@ -419,3 +419,41 @@ def test_token_importance_and_topk_selection():
             ref = np.maximum(ref, np.abs(X[r].astype(np.float64)))
     assert np.array_equal(xs, ref.astype(np.float32))
     assert np.array_equal(orc.x_stat_topk_max(X, np.ones(N, bool)), orc.x_stat_max(X))
+
+
+# ------------------------------------------- brute force, randomised shapes
+def test_brute_force_random_tiny_layers():
+    """The fixed brute-force cases above, widened: random tiny shapes, group sizes, bit widths,
+    outlier strengths and alpha grids (hypothesis, derandomised), oracle against the pure-Python
+    loops - losses to 1e-12, codes, zero points and steps exactly."""
+    from hypothesis import given, settings, strategies as st
+
+    @settings(max_examples=60, deadline=None, derandomize=True)
+    @given(seed=st.integers(0, 10_000), n=st.integers(1, 6), groups=st.integers(1, 3), g=st.sampled_from([2, 4]),
+           co=st.integers(1, 5), bits=st.integers(2, 5), whole_row=st.booleans(), mult=st.sampled_from([1.0, 8.0, 60.0]),
+           abits=st.sampled_from([0, 0, 2, 4, 8]))
+    def run(seed, n, groups, g, co, bits, whole_row, mult, abits):
+        ci = g * groups
+        X, W, w = wl.tiny_layer(seed, n, ci, co, mult=mult)
+        Y = orc.ref_output(X, W).astype(np.float32)
+        group = 0 if whole_row else g
+        alphas = [0.0, 0.3, 0.65, 0.95]
+        res = orc.scale_search(X, W, Y, w, bits, group, np.array(alphas, np.float32), act_bits=abits)
+        xs_b = brute.brute_x_stat(X.tolist())
+        assert [float(v) for v in xs_b] == res["x_stat"].tolist()
+        for k, a in enumerate(alphas):
+            s_b = brute.brute_scale(xs_b, a)
+            assert [float(v) for v in s_b] == res["s_table"][k].tolist()
+            if abits:
+                Lb = brute.brute_loss_aq(X.tolist(), W.tolist(), Y.tolist(), w.tolist(), s_b, bits, group, abits)
+            else:
+                Lb = brute.brute_loss(X.tolist(), W.tolist(), Y.tolist(), w.tolist(), s_b, bits, group)
+            assert abs(res["losses"][k] - Lb) <= 1e-12 * abs(Lb) + 1e-300
+            codes, zp, delta, deq = orc.fake_quant(W, res["s_table"][k], bits, group)
+            for o in range(co):
+                cb, zb, db, qb = brute.brute_fake_quant_row(W[o].tolist(), s_b, bits, group)
+                assert cb == codes[o].tolist() and zb == zp[o].tolist()
+                assert [float(v) for v in db] == delta[o].tolist()
+        assert res["best_idx"] == int(np.argmin(res["losses"]))
+
+    run()
