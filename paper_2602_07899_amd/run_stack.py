@@ -63,14 +63,15 @@ def topk_xstat_fn(sw, n_samples, p, dev, dtype, frac=0.5):
     import torch
     per = sw.seq_len
     g = torch.Generator(device=dev)
-    amp = torch.cat([torch.exp(torch.randn(sw.n_vis, generator=g.manual_seed(sw.seed * 1000 + 777), device=dev) * 1.5 - 4.0),
-                     torch.exp(torch.randn(sw.n_txt, generator=g, device=dev) * 0.5)])
+    g.manual_seed(sw.seed * 1000 + 777)
+    amp_vis = torch.exp(torch.randn(sw.n_vis, generator=g, device=dev) * 1.5 - 4.0)
+    amp_txt = torch.exp(torch.randn(sw.n_txt, generator=g, device=dev) * 0.5)
+    amp = torch.cat([amp_vis, amp_txt]).repeat(n_samples)[:, None]
 
     def fn(layer, names, X):
         c = X.shape[1]
-        g.manual_seed((sw.seed * 1000 + layer) * 16 + len(names) + (3 if c != sw.hidden else 0))
-        G = (torch.randn((n_samples * per, c), generator=g, device=dev, dtype=torch.float32)
-             * amp.repeat(n_samples)[:, None]).to(dtype)
+        g.manual_seed((sw.seed * 1000 + layer) * 16 + gstack.GROUPS.index(tuple(names)))
+        G = (torch.randn((n_samples * per, c), generator=g, device=dev, dtype=torch.float32) * amp).to(dtype)
         sum_n = torch.empty(per, dtype=torch.float64, device=dev)
         tlq.token_importance(G, n_samples, p, sum_n)
         mask = torch.empty(per, dtype=torch.uint8, device=dev)
