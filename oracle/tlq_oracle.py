@@ -48,7 +48,9 @@ Parity pins (see tests/test_oracle_pins.py): brute force on tiny layers
 alpha=1 closed forms, uniform-weight MSE, smoothing identity with an identity
 quantiser, grid idempotence, Delta^2/12 error energy (Sec. 2.2), power-of-two
 scale invariance, max-code closed form for the symmetric variant.
-Every function of this module has at least one such pin.  Not pinned, and not
+Every function of this module has at least one such pin; the sequential-chain
+module (oracle/chain.py) is pinned by tests/test_oracle_chain_pins.py and the
+decoder-stack module (oracle/stack.py) by tests/test_oracle_stack_pins.py.  Not pinned, and not
 pinnable here: that these definitions reproduce the paper's downstream accuracy
 tables - that needs the trained models and evaluation suites (parity unpinned
 for accuracy).
@@ -325,18 +327,8 @@ def apply_best(X, W, s, bits, group, symmetric=False, act_bits=0):
 
 
 # --------------------------------------------------------------------------
-# diagnostic: rounding-aware variant (not the pass/fail reference)
+# storage rounding helper for bf16 test inputs
 # --------------------------------------------------------------------------
-def folded_operand(deq, s, dtype=np.float16):
-    """deq / s in float32 (IEEE division) rounded to a 16-bit operand type.
-    Diagnostic only: mirrors the one place where a 16-bit matrix pipeline
-    must round, to separate kernel bugs from operand-rounding effects."""
-    w = (np.asarray(deq, np.float32) / np.asarray(s, np.float32)[None, :]).astype(np.float32)
-    if dtype == np.float16:
-        return w.astype(np.float16)
-    return round_to_bf16(w)
-
-
 def round_to_bf16(a):
     """Round float32 to bfloat16 (round-half-to-even), returned as float32."""
     a = np.ascontiguousarray(a, dtype=np.float32)
