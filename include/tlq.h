@@ -92,6 +92,21 @@ tlq_status tlq_x_stat(const void* X, int64_t n_tok, int64_t c_in, int64_t ldx,
                       const tlq_params* p, float* x_stat,
                       void* workspace, size_t workspace_bytes, void* stream);
 
+/* ---- tlq_x_stat for callers that cannot allocate device memory: code under HIP graph
+ * capture, tight serving loops, harnesses that forbid hipMalloc.  Same kernels, same
+ * result bit for bit as tlq_x_stat, but the partial sums live in a fixed 16 MiB device
+ * array inside the library (one copy per GPU, held until the process ends) instead of a
+ * caller workspace.  The call allocates and frees nothing, on the device or through any
+ * library.  Limits: c_in <= TLQ_X_STAT_STATIC_MAX_C_IN (TLQ_ERR_WORKSPACE beyond it);
+ * per-kernel timing must be off (TLQ_ERR_UNSUPPORTED while tlq_profile_enable(1) is in
+ * force, because timing creates HIP events).  The stream must belong to the device that is
+ * current at the call.  All calls on one GPU share that GPU's array: calls that overlap in
+ * time on one GPU (different streams or threads) race on it and give wrong results;
+ * serialise them.  Nothing in the array needs to survive between calls. */
+#define TLQ_X_STAT_STATIC_MAX_C_IN 16384
+tlq_status tlq_x_stat_static(const void* X, int64_t n_tok, int64_t c_in, int64_t ldx,
+                             const tlq_params* p, float* x_stat, void* stream);
+
 /* ---- gradient-guided token selection (Sec. 3.1.2).  G holds per-sample gradients with
  * respect to the layer input, sample major: [n_samples * n_pos, c] x_dtype.
  *   tlq_token_importance: sum_n[n] = sum_b ||g_{b,n}||, n < n_pos (gradient-statistic eq.);
@@ -246,6 +261,7 @@ tlq_status tlq_residual_add(const void* H, int64_t ldh, const void* Z, int64_t l
  * kernel name, number of launches, total milliseconds, and the total
  * algorithmic work (flops for the contraction kernels, bytes otherwise). */
 tlq_status tlq_profile_enable(int on);
+int tlq_profile_enabled(void);
 tlq_status tlq_profile_reset(void);
 tlq_status tlq_profile_collect(void);
 int tlq_profile_count(void);

@@ -67,6 +67,11 @@ tlq_status tlq_profile_enable(int on) {
   return TLQ_OK;
 }
 
+int tlq_profile_enabled(void) {
+  std::lock_guard<std::mutex> lk(g_mu);
+  return g_on ? 1 : 0;
+}
+
 tlq_status tlq_profile_collect(void) {
   std::lock_guard<std::mutex> lk(g_mu);
   for (Rec& r : g_recs) {

@@ -48,6 +48,7 @@ _SIGNATURES = {
     "tlq_version": (C.c_int, []),
     "tlq_x_stat_workspace_bytes": (_SZ, [_I64, _I64]),
     "tlq_x_stat": (C.c_int, [_P, _I64, _I64, _I64, _PP, _P, _P, _SZ, _P]),
+    "tlq_x_stat_static": (C.c_int, [_P, _I64, _I64, _I64, _PP, _P, _P]),
     "tlq_token_importance_workspace_bytes": (_SZ, [_I64, _I64]),
     "tlq_token_importance": (C.c_int, [_P, _I64, _I64, _I64, _I64, _I32, _PP, _P, _P, _SZ, _P]),
     "tlq_topk_mask": (C.c_int, [_P, _I64, _I64, _P, _P]),
@@ -69,6 +70,7 @@ _SIGNATURES = {
     "tlq_silu_mul": (C.c_int, [_P, _I64, _P, _I64, _I64, _I64, _PP, _P, _I64, _P]),
     "tlq_residual_add": (C.c_int, [_P, _I64, _P, _I64, _I64, _I64, _PP, _P, _I64, _P]),
     "tlq_profile_enable": (C.c_int, [C.c_int]),
+    "tlq_profile_enabled": (C.c_int, []),
     "tlq_profile_reset": (C.c_int, []),
     "tlq_profile_collect": (C.c_int, []),
     "tlq_profile_count": (C.c_int, []),
@@ -135,6 +137,14 @@ def x_stat(X, p, out, workspace=None):
     ws = workspace if workspace is not None else _ws(x_stat_workspace_bytes(n, c), X)
     _check(lib().tlq_x_stat(_ptr(X), n, c, _ld(X), C.byref(p), _ptr(out), _ptr(ws), ws.numel(),
                             _stream()), "tlq_x_stat")
+    return out
+
+
+def x_stat_static(X, p, out):
+    """tlq_x_stat without a workspace: partial sums go to the library's fixed device array."""
+    n, c = X.shape
+    _check(lib().tlq_x_stat_static(_ptr(X), n, c, _ld(X), C.byref(p), _ptr(out), _stream()),
+           "tlq_x_stat_static")
     return out
 
 
