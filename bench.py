@@ -4,14 +4,23 @@
 
 A step is one pass of the whole hot path (x_stat, scale table, fake
 quantisation of every candidate, fused contraction + weighted loss, final
-combine and selection) over the seven linears of one 7B-class decoder layer
-with 16 x 640 synthetic calibration tokens and a 20-point alpha grid:
-7 x 20 = 140 candidate evaluations.  Inputs (X, W, Y_ref, token weights) are
-resident in HBM before the timed region.  Prints ONE JSON line.
+combine and selection) over the seven linears of one decoder layer with a
+20-point alpha grid: 7 x 20 = 140 candidate evaluations.  The headline
+workload is the largest one-GPU layer configuration, the 13B-class layer
+with 128 x 1200 = 153,600 synthetic calibration tokens (cfg4_13b_w4); the
+7B-class layer with 16 x 640 tokens (cfg2_7b_w4) is timed in the same run and
+reported under "secondary".  Inputs (X, W, Y_ref, token weights) are resident
+in HBM before the timed region.  Prints ONE JSON line.
+
+Outside the timed region the CPU oracle is timed on a bounded sample of each
+workload ("cpu_baseline") and its losses on that sample are compared with the
+library's losses on the same inputs ("parity_max_rel").
 """
 from __future__ import annotations
 
 import argparse
+import concurrent.futures as cf
+import hashlib
 import json
 import os
 import sys
@@ -23,35 +32,188 @@ if ROOT not in sys.path:
 
 METRIC = "candidate-scale evals/sec per layer + fused-kernel TFLOP/s (% fp16 MFMA peak)"
 PEAK_FP16_TFLOPS = 2500.0      # MI355X dense fp16 MFMA peak (published)
-# Bytes per gemm_loss launch that cross the L2/fabric boundary, from two rocprofv3 --pmc
-# runs of this file (FETCH_SIZE, WRITE_SIZE), each scaled by what the same counter reads
-# for the known-size calibration copy below (x1.999 and x1.000); summary under profiles/.
-MEASURED_TRAFFIC_BYTES_PER_LAUNCH = 1.998e10
+HOST_THREADS = 16              # the GPU machine's CPU share
 
 
-def cpu_baseline(wl, orc, workload):
-    """Time the oracle, as it stands, on a bounded sample of the same workload:
-    the q_proj-shaped linear with all of its 10240 tokens and the whole
-    20-point grid (one of the step's seven searches).  Reported as candidate
-    evaluations per second."""
-    import numpy as np
+def log(msg):
+    print(f"bench.py: {msg}", file=sys.stderr, flush=True)
+
+
+def source_fingerprint():
+    """sha256 over the library's sources: stored counter readings are only quoted for the
+    build they were taken from."""
+    h = hashlib.sha256()
+    csrc = os.path.join(ROOT, "paper_2602_07899_amd", "csrc")
+    files = sorted(os.path.join(csrc, f) for f in os.listdir(csrc) if f.endswith((".hip", ".h")))
+    files.append(os.path.join(ROOT, "include", "tlq.h"))
+    for f in files:
+        h.update(os.path.basename(f).encode())
+        h.update(open(f, "rb").read())
+    return h.hexdigest()[:16]
+
+
+def recorded_traffic(workload_name):
+    """Bytes per gemm_loss launch that cross the L2/fabric boundary, from the rocprofv3 --pmc
+    runs summarised in profiles/traffic.json (written by paper_2602_07899_amd/record_traffic.py);
+    None unless that record was taken from exactly this source tree."""
+    path = os.path.join(ROOT, "profiles", "traffic.json")
+    if not os.path.exists(path):
+        return None
+    rec = json.load(open(path))
+    if rec.get("source_fingerprint") != source_fingerprint():
+        return None
+    return rec.get("gemm_loss_bytes_per_launch", {}).get(workload_name)
+
+
+def host_cores():
     try:
         from threadpoolctl import threadpool_info
-        cores = max([i.get("num_threads", 1) for i in threadpool_info()] or [os.cpu_count() or 1])
+        return int(max([i.get("num_threads", 1) for i in threadpool_info()] or [os.cpu_count() or 1]))
     except Exception:
-        cores = os.cpu_count() or 1
-    cand = list(range(workload.n_alpha))
-    X = wl.make_tokens(workload, 0)
-    W = wl.make_weight(workload, 0)
-    w = wl.make_token_weights(workload, 0)
-    al = wl.alpha_grid(workload.n_alpha)[cand]
+        return int(os.cpu_count() or 1)
+
+
+def resident_inputs(wl, tlq, torch, workload, dev, p, want_abs_sum_of=None):
+    """Draw every linear's inputs from the seeded per-sample generators (host threads), place
+    them in HBM and form Y_ref with the library's own f_fp GEMM.  Returns the per-linear
+    tuples and, for linear `want_abs_sum_of`, the float64 column sums of |X| (the oracle's
+    x_stat numerator, accumulated while the samples pass through the host)."""
+    import numpy as np
+    per = workload.n_vis + workload.n_txt
+    layers, abs_sum = [], None
+    for li, spec in enumerate(workload.linears):
+        X = torch.empty((workload.n_tok, spec.c_in), dtype=torch.float16, device=dev)
+        keep = li == want_abs_sum_of
+        if keep:
+            abs_sum = np.zeros(spec.c_in, np.float64)
+
+        def one(b):
+            xb = wl.make_sample_tokens(workload, li, b).astype(np.float16)
+            return b, xb, (np.abs(xb.astype(np.float64)).sum(axis=0) if keep else None)
+
+        with cf.ThreadPoolExecutor(HOST_THREADS) as ex:
+            for b, xb, s in ex.map(one, range(workload.n_samples)):
+                X[b * per:(b + 1) * per].copy_(torch.from_numpy(xb))
+                if keep:
+                    abs_sum += s
+        W = torch.from_numpy(wl.make_weight(workload, li)).to(dev)
+        w = torch.from_numpy(wl.make_token_weights(workload, li)).to(dev)
+        Y = torch.empty((workload.n_tok, spec.c_out), dtype=torch.float16, device=dev)
+        tlq.ref_output(X, W, Y, p)
+        out = (torch.empty(spec.c_in, dtype=torch.float32, device=dev),
+               torch.empty(1, dtype=torch.int32, device=dev),
+               torch.empty(workload.n_alpha, dtype=torch.float32, device=dev))
+        layers.append((spec, X, W, Y, w, out))
+        log(f"{workload.name}: inputs of {spec.name} resident")
+    return layers, abs_sum
+
+
+def timed_workload(wl, tlq, torch, workload, layers, p, al, workspace, steps, warmup, act_bits):
+    """W warm-up steps, then exactly K timed steps bracketed by device synchronisation; HIP
+    events around every kernel on the launch stream give the per-kernel figures."""
+    def step():
+        for spec, X, W, Y, w, (best, idx, losses) in layers:
+            tlq.scale_search(X, W, Y, w, al, p, best, idx, losses, workspace=workspace)
+
+    for _ in range(warmup):
+        step()
+    torch.cuda.synchronize()
+    tlq.profile_reset()
+    tlq.profile_enable(True)
+    t0 = time.perf_counter()
+    for _ in range(steps):
+        step()
+    torch.cuda.synchronize()
+    dt = time.perf_counter() - t0
+    tlq.profile_enable(False)
+    kernels = {k.name: k for k in tlq.profile_read()}
+
+    per_linear = []
+    for spec, X, W, Y, w, (best, idx, losses) in layers:
+        ms = []
+        for _ in range(3):
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0.record()
+            tlq.scale_search(X, W, Y, w, al, p, best, idx, losses, workspace=workspace)
+            e1.record()
+            e1.synchronize()
+            ms.append(e0.elapsed_time(e1))
+        m = sorted(ms)[1]
+        per_linear.append({"linear": f"{spec.name}:{spec.c_out}x{spec.c_in}", "ms_per_search": round(m, 4),
+                           "evals_per_s": workload.n_alpha / (m * 1e-3),
+                           "search_tflops": 2.0 * workload.n_tok * spec.c_in * spec.c_out * workload.n_alpha
+                                            / (m * 1e-3) / 1e12})
+    evals = len(layers) * workload.n_alpha * steps
+    g = kernels["gemm_loss"]
+    tflops = g.total_work / (g.total_ms * 1e-3) / 1e12
+    return {
+        "value": evals / dt, "ms_per_step": dt / steps * 1e3,
+        "config": {"workload": workload.name,
+                   "linears": [f"{s.name}:{s.c_out}x{s.c_in}" for s in workload.linears],
+                   "n_tok": workload.n_tok, "bits": workload.bits, "group": workload.group,
+                   "n_alpha": workload.n_alpha, "evals_per_step": len(layers) * workload.n_alpha,
+                   "act_bits": act_bits},
+        "fused_kernel_tflops": tflops, "pct_fp16_mfma_peak": 100.0 * tflops / PEAK_FP16_TFLOPS,
+        "roofline": {"bound": "mfma", "kernel": "gemm_loss", "achieved": tflops, "peak": PEAK_FP16_TFLOPS,
+                     "unit": "TFLOP/s", "frac": tflops / PEAK_FP16_TFLOPS,
+                     "avg_launch_ms": g.total_ms / g.launches, "flops_per_launch": g.total_work / g.launches,
+                     "traffic": recorded_traffic(workload.name) if act_bits == 0 else None},
+        "kernels": {k.name: {"launches": k.launches, "ms": round(k.total_ms, 4),
+                             "rate": (k.total_work / (k.total_ms * 1e-3) / 1e9) if k.total_ms > 0 else None,
+                             "rate_unit": "GFLOP/s" if k.name.startswith("gemm") else "GB/s"}
+                    for k in kernels.values()},
+        "per_linear": per_linear,
+        "best_alpha_index": [int(l[5][1].item()) for l in layers],
+    }
+
+
+def oracle_leg(wl, tlq, torch, orc, workload, dev, p, n_samples, cands, x_abs_sum):
+    """The oracle, as it stands, timed on a bounded sample of the workload's first linear:
+    the first `n_samples` calibration samples and the candidates `cands` of the grid, with the
+    channel statistic of ALL tokens.  The library then searches the same inputs (X, W, the
+    oracle's Y_ref, token weights, the oracle's x_stat) and the two sets of losses are compared.
+    evals/s counts full-size-equivalent candidate evaluations: candidates x (tokens in the
+    sample / tokens of the workload) per second - an extrapolation unless the sample is whole."""
+    import numpy as np
+    li = 0
+    spec = workload.linears[li]
+    per = workload.n_vis + workload.n_txt
+    n = n_samples * per
+    X = wl.make_tokens(workload, li, samples=range(n_samples))
+    W = wl.make_weight(workload, li)
+    w = wl.make_token_weights(workload, li)[:n]
+    al = wl.alpha_grid(workload.n_alpha)[list(cands)]
+    x_stat = (x_abs_sum / np.float64(workload.n_tok)).astype(np.float32)   # definition of x_stat_mean, streamed
+    if n == workload.n_tok:
+        assert np.array_equal(x_stat, orc.x_stat_mean(X))
     Y = orc.ref_output(X, W).astype(np.float16)
     t0 = time.perf_counter()
-    orc.scale_search(X, W, Y, w, workload.bits, workload.group, al)
+    ref = orc.scale_search(X, W, Y, w, workload.bits, workload.group, al, x_stat=x_stat)
     dt = time.perf_counter() - t0
-    return {"value": len(cand) / dt, "unit": "evals/s", "cores": int(cores), "kind": "oracle",
-            "sample": f"{workload.name} q_proj 4096x4096, all {X.shape[0]} tokens, "
-                      f"{len(cand)} of {workload.n_alpha} candidates, {dt:.1f} s of numpy fp64"}
+    frac = n / workload.n_tok
+    whole = n == workload.n_tok
+    base = {"value": len(cands) * frac / dt, "unit": "evals/s", "cores": host_cores(), "kind": "oracle",
+            "extrapolated": not whole,
+            "sample": f"{workload.name} {spec.name} {spec.c_out}x{spec.c_in}, "
+                      f"{n} of {workload.n_tok} tokens ({'all' if whole else 'the first'} {n_samples} samples), "
+                      f"{len(cands)} of {workload.n_alpha} candidates, {dt:.1f} s of numpy fp64"
+                      + ("" if whole else f"; scaled by {frac:.5f} to full-size evaluations")}
+    # the library on exactly these inputs
+    t = lambda a: torch.from_numpy(np.ascontiguousarray(a)).to(dev)
+    best = torch.empty(spec.c_in, dtype=torch.float32, device=dev)
+    idx = torch.empty(1, dtype=torch.int32, device=dev)
+    losses = torch.empty(len(cands), dtype=torch.float32, device=dev)
+    tlq.scale_search(t(X), t(W), t(Y), t(w), t(al), p, best, idx, losses, x_stat_in=t(x_stat))
+    torch.cuda.synchronize()
+    got = losses.cpu().numpy().astype(np.float64)
+    rel = np.abs(got - ref["losses"]) / ref["losses"]
+    order = np.sort(ref["losses"])
+    near_tie = len(order) > 1 and (order[1] - order[0]) <= 1e-3 * order[0]
+    parity = {"parity_max_rel": float(rel.max()), "tolerance": 1e-3, "candidates": len(cands), "tokens": n,
+              "same_choice": bool(int(idx.item()) == ref["best_idx"]) or bool(near_tie),
+              "scales_equal": bool(np.array_equal(best.cpu().numpy(), ref["best_scales"]))
+                              if int(idx.item()) == ref["best_idx"] else None}
+    return base, parity
 
 
 def mfma_ceiling():
@@ -76,10 +238,10 @@ def main():
     ap.add_argument("--act-bits", type=int, default=0,
                     help="also quantise activations per token inside every candidate (the paper's "
                          "W4A8 / W4A6 objective); 0 = the weight-only headline workload")
-    ap.add_argument("--workload", default="cfg2_7b_w4", choices=("cfg2_7b_w4", "cfg4_13b_w4"),
-                    help="cfg2_7b_w4 is the benchmark workload; cfg4_13b_w4 (13B-class layer, 153,600 tokens) "
-                         "measures the same step at the larger shapes (no CPU baseline, no stored traffic figure)")
-    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--workload", default="cfg4_13b_w4", choices=("cfg4_13b_w4", "cfg2_7b_w4"),
+                    help="headline workload; the default run also times cfg2_7b_w4 as a secondary block")
+    ap.add_argument("--no-secondary", action="store_true", help="skip the secondary workload")
+    ap.add_argument("--no-cpu-baseline", action="store_true", help="skip the oracle timing and parity legs")
     ap.add_argument("--no-ceiling", action="store_true",
                     help="skip the register-only MFMA ceiling measurement (context only)")
     args = ap.parse_args()
@@ -88,7 +250,6 @@ def main():
               "run with --gpus 1", file=sys.stderr)
         sys.exit(2)
 
-    import numpy as np
     import torch
 
     from paper_2602_07899_amd import tlq
@@ -98,106 +259,62 @@ def main():
         print("bench.py: no GPU visible", file=sys.stderr)
         sys.exit(2)
     dev = torch.device("cuda:0")
-    workload = wl.CONFIGS[args.workload]
-    headline = args.workload == "cfg2_7b_w4"
-    p = tlq.params(bits=workload.bits, group=workload.group, act_bits=args.act_bits, x_dtype=tlq.F16,
-                   yref_dtype=tlq.F16)
-    al = torch.from_numpy(wl.alpha_grid(workload.n_alpha)).to(dev)
+    oracle_on = not args.no_cpu_baseline and args.act_bits == 0
+    # bounded oracle samples: (calibration samples, candidates) - about 10-20 s of numpy fp64 each
+    ORACLE_SAMPLE = {"cfg4_13b_w4": (8, tuple(range(0, 20, 2))), "cfg2_7b_w4": (16, tuple(range(20)))}
 
-    # ---- inputs resident in HBM (Y_ref = f_fp output through the library's own GEMM)
-    layers = []
-    ws_bytes = 0
-    for li, spec in enumerate(workload.linears):
-        X = torch.from_numpy(wl.make_tokens(workload, li)).to(dev)
-        W = torch.from_numpy(wl.make_weight(workload, li)).to(dev)
-        w = torch.from_numpy(wl.make_token_weights(workload, li)).to(dev)
-        Y = torch.empty((workload.n_tok, spec.c_out), dtype=torch.float16, device=dev)
-        tlq.ref_output(X, W, Y, p)
-        out = (torch.empty(spec.c_in, dtype=torch.float32, device=dev),
-               torch.empty(1, dtype=torch.int32, device=dev),
-               torch.empty(workload.n_alpha, dtype=torch.float32, device=dev))
-        layers.append((spec, X, W, Y, w, out))
-        print(f"bench.py: inputs of {spec.name} resident", file=sys.stderr, flush=True)
-        ws_bytes = max(ws_bytes, tlq.scale_search_workspace_bytes(workload.n_tok, spec.c_in, spec.c_out,
-                                                                  workload.n_alpha, p))
-    workspace = torch.empty(ws_bytes, dtype=torch.uint8, device=dev)
-    # one device-to-device copy of known size (reads and writes 83,886,080 bytes): the
-    # calibration kernel for the FETCH_SIZE / WRITE_SIZE counters in profiling runs
-    calib = torch.empty_like(layers[0][1])
-    calib.copy_(layers[0][1])
-    torch.cuda.synchronize()
+    def run(name):
+        workload = wl.CONFIGS[name]
+        p = tlq.params(bits=workload.bits, group=workload.group, act_bits=args.act_bits, x_dtype=tlq.F16,
+                       yref_dtype=tlq.F16)
+        al = torch.from_numpy(wl.alpha_grid(workload.n_alpha)).to(dev)
+        layers, abs_sum = resident_inputs(wl, tlq, torch, workload, dev, p, want_abs_sum_of=0 if oracle_on else None)
+        ws_bytes = max(tlq.scale_search_workspace_bytes(workload.n_tok, s.c_in, s.c_out, workload.n_alpha, p)
+                       for s in workload.linears)
+        workspace = torch.empty(ws_bytes, dtype=torch.uint8, device=dev)
+        # one device-to-device copy of known size (reads and writes 83,886,080 bytes): the
+        # calibration kernel for the FETCH_SIZE / WRITE_SIZE counters in profiling runs
+        src = layers[0][1].view(-1)[:41943040]
+        torch.empty_like(src).copy_(src)
+        torch.cuda.synchronize()
+        res = timed_workload(wl, tlq, torch, workload, layers, p, al, workspace, args.steps, args.warmup,
+                             args.act_bits)
+        log(f"{name}: {res['value']:.1f} evals/s, gemm_loss {res['fused_kernel_tflops']:.1f} TFLOP/s")
+        if oracle_on:
+            from oracle import tlq_oracle as orc
+            ns, cands = ORACLE_SAMPLE[name]
+            p0 = tlq.params(bits=workload.bits, group=workload.group, x_dtype=tlq.F16, yref_dtype=tlq.F16)
+            res["cpu_baseline"], res["parity"] = oracle_leg(wl, tlq, torch, orc, workload, dev, p0, ns, cands, abs_sum)
+            log(f"{name}: oracle {res['cpu_baseline']['value']:.4f} evals/s, parity_max_rel "
+                f"{res['parity']['parity_max_rel']:.2e}")
+        del layers, workspace
+        torch.cuda.empty_cache()
+        return res
 
-    def step():
-        for spec, X, W, Y, w, (best, idx, losses) in layers:
-            tlq.scale_search(X, W, Y, w, al, p, best, idx, losses, workspace=workspace)
-
-    for _ in range(args.warmup):
-        step()
-    torch.cuda.synchronize()
-    tlq.profile_reset()
-    tlq.profile_enable(True)          # HIP events around every kernel, on the launch stream
-    t0 = time.perf_counter()
-    for _ in range(args.steps):
-        step()
-    torch.cuda.synchronize()
-    dt = time.perf_counter() - t0
-    tlq.profile_enable(False)
-    kernels = {k.name: k for k in tlq.profile_read()}
-
-    # per linear shape (outside the timed region): median of 3 searches, events on the launch stream
-    per_linear = []
-    for spec, X, W, Y, w, (best, idx, losses) in layers:
-        ms = []
-        for _ in range(3):
-            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-            e0.record()
-            tlq.scale_search(X, W, Y, w, al, p, best, idx, losses, workspace=workspace)
-            e1.record()
-            e1.synchronize()
-            ms.append(e0.elapsed_time(e1))
-        m = sorted(ms)[1]
-        per_linear.append({"linear": f"{spec.name}:{spec.c_out}x{spec.c_in}", "ms_per_search": round(m, 4),
-                           "evals_per_s": workload.n_alpha / (m * 1e-3),
-                           "search_tflops": 2.0 * workload.n_tok * spec.c_in * spec.c_out * workload.n_alpha
-                                            / (m * 1e-3) / 1e12})
-
-    evals = len(layers) * workload.n_alpha * args.steps
-    g = kernels["gemm_loss"]
-    tflops = g.total_work / (g.total_ms * 1e-3) / 1e12
-    flops_per_launch = g.total_work / g.launches
-    best_idx = [int(l[5][1].item()) for l in layers]
-
+    head = run(args.workload)
     result = {
-        "metric": METRIC, "value": evals / dt, "unit": "evals/s", "n_gpus": 1,
-        "steps": args.steps, "warmup": args.warmup, "ms_per_step": dt / args.steps * 1e3,
+        "metric": METRIC, "value": head["value"], "unit": "evals/s", "n_gpus": 1,
+        "steps": args.steps, "warmup": args.warmup, "ms_per_step": head["ms_per_step"],
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "f16",
         "data": "synthetic",
-        "config": {"workload": workload.name, "linears": [f"{s.name}:{s.c_out}x{s.c_in}" for s in workload.linears],
-                   "n_tok": workload.n_tok, "bits": workload.bits, "group": workload.group,
-                   "n_alpha": workload.n_alpha, "evals_per_step": len(layers) * workload.n_alpha,
-                   "act_bits": args.act_bits},
-        "fused_kernel_tflops": tflops, "pct_fp16_mfma_peak": 100.0 * tflops / PEAK_FP16_TFLOPS,
-        "roofline": {"bound": "mfma", "kernel": "gemm_loss", "achieved": tflops, "peak": PEAK_FP16_TFLOPS,
-                     "unit": "TFLOP/s", "frac": tflops / PEAK_FP16_TFLOPS,
-                     "avg_launch_ms": g.total_ms / g.launches, "flops_per_launch": flops_per_launch,
-                     "traffic": MEASURED_TRAFFIC_BYTES_PER_LAUNCH if (args.act_bits == 0 and headline) else None},
-        "kernels": {k.name: {"launches": k.launches, "ms": round(k.total_ms, 4),
-                             "rate": (k.total_work / (k.total_ms * 1e-3) / 1e9) if k.total_ms > 0 else None,
-                             "rate_unit": "GFLOP/s" if k.name.startswith("gemm") else "GB/s"}
-                    for k in kernels.values()},
-        "per_linear": per_linear,
-        "best_alpha_index": best_idx,
-        "peak_hbm_bytes": int(torch.cuda.max_memory_allocated()),
-        # the paper publishes no speed figure for this path; its cost figures are about memory
-        "paper_context": "paper (Sec. 3.2.2 and its memory table): calibrating a 7B VLM on 128 samples takes one "
-                         "A100-80GB with the prior layer-wise method and 3 x RTX3090-24GB with its distributed "
-                         "split (7.1-18.8 GB peak per GPU); no calibration time, throughput or kernel timing is given",
     }
+    for k in ("config", "fused_kernel_tflops", "pct_fp16_mfma_peak", "roofline", "cpu_baseline", "parity",
+              "kernels", "per_linear", "best_alpha_index"):
+        if k in head:
+            result[k] = head[k]
+    if not args.no_secondary:
+        other = "cfg2_7b_w4" if args.workload == "cfg4_13b_w4" else "cfg4_13b_w4"
+        sec = run(other)
+        sec["unit"] = "evals/s"
+        result["secondary"] = sec
+    result["peak_hbm_bytes"] = int(torch.cuda.max_memory_allocated())
+    result["source_fingerprint"] = source_fingerprint()
+    # the paper publishes no speed figure for this path; its cost figures are about memory
+    result["paper_context"] = ("paper (Sec. 3.2.2 and its memory table): calibrating a 7B VLM on 128 samples takes one "
+                               "A100-80GB with the prior layer-wise method and 3 x RTX3090-24GB with its distributed "
+                               "split (7.1-18.8 GB peak per GPU); no calibration time, throughput or kernel timing is given")
     if not args.no_ceiling:
         result["mfma_ceiling"] = mfma_ceiling()
-    if not args.no_cpu_baseline and args.act_bits == 0 and headline:
-        from oracle import tlq_oracle as orc
-        result["cpu_baseline"] = cpu_baseline(wl, orc, workload)
     print(json.dumps(result))
 
 

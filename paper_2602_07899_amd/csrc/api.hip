@@ -143,6 +143,11 @@ const char* tlq_status_string(int s) {
 
 int tlq_version(void) { return TLQ_VERSION; }
 
+// host-side self check of the contraction kernels' block -> tile map (no GPU work)
+int64_t tlq_selftest_tile_map(int64_t n_tok, int64_t c_in, int64_t c_out, int32_t n_cand, int64_t* blocks) {
+  return tile_map_defects(n_tok, c_in, c_out, n_cand, blocks);
+}
+
 // ------------------------------------------------------------------------ S0
 size_t tlq_x_stat_workspace_bytes(int64_t n_tok, int64_t c_in) {
   if (n_tok <= 0 || c_in <= 0) return 0;

@@ -125,6 +125,7 @@ struct GemmArgs {
   void* Yout; int64_t ldo; int yout_dtype;
 };
 void gemm_tile_counts(int64_t n_tok, int64_t c_out, int64_t* tiles_o, int64_t* tiles_t);
+int64_t tile_map_defects(int64_t n_tok, int64_t c_in, int64_t c_out, int n_cand, int64_t* blocks_out);
 hipError_t launch_gemm_loss(const GemmArgs& a, hipStream_t stream);
 hipError_t launch_gemm_store(const GemmArgs& a, hipStream_t stream);
 

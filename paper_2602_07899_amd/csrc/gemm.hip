@@ -20,6 +20,7 @@
 // the fragment reads and for the tile writes alike.
 // Two LDS stages: the global loads of k-tile i+1 are issued before the MFMAs of
 // k-tile i and written to the other stage afterwards; one barrier per k-tile.
+#include <cstdlib>
 #include <utility>
 
 #include "common.h"
@@ -58,7 +59,8 @@ struct GemmDev {
   void* Yout; int64_t ldo; int odt;
   int tiles_o, tiles_t, npo, npt;  // tiles per candidate and patches per candidate
   int64_t n_patches;
-  int cpt;  // token patches per chunk (see make_dev)
+  int cpt;          // token patches per chunk (see make_dev)
+  int rag, rag_pt;  // tile rows of the last, incomplete patch row (0 = none) and its patch width in tiles
 };
 
 __device__ __forceinline__ int swz(int row, int chunk) { return chunk ^ ((row >> 1) & 7); }
@@ -323,6 +325,45 @@ __device__ __forceinline__ void tile_epilogue(const GemmDev& a, f32x16 (&acc)[FA
   }
 }
 
+// Block id -> (candidate, tile row, tile column).  Blocks are dealt to the 8 XCDs round-robin by
+// block id, so block id = (round, xcd, slot) and every XCD works on one patch of PATCH_O x PATCH_T
+// tiles at a time (32 CUs = 32 tiles sharing 4 weight panels and 8 token panels in its L2).
+// Patch order: chunks of cpt token patches; inside a chunk, for every output patch row, every
+// candidate visits the chunk's token patches.  The chunk's tokens and the row's slice of Y_ref are
+// thus shared by all candidates while they are hot in the last-level cache, and each candidate's
+// weights are streamed once per chunk.  When tiles_o is not a multiple of PATCH_O the last patch row
+// has `rag` tile rows and uses patches of rag x rag_pt tiles, so that (nearly) every slot of a patch
+// is a live tile.  Returns false for a slot that has no tile.
+__host__ __device__ __forceinline__ bool decode_tile(const GemmDev& a, int64_t bid, int& cand, int& to, int& tt) {
+  const int64_t round = bid / (8 * PATCH_O * PATCH_T);
+  const int within = (int)(bid % (8 * PATCH_O * PATCH_T));
+  const int64_t patch = round * 8 + (within & 7);
+  const int slot = within >> 3;
+  if (patch >= a.n_patches) return false;
+  const int n_full = a.rag ? a.npo - 1 : a.npo;
+  const int ragp_full = a.rag ? (a.cpt * PATCH_T + a.rag_pt - 1) / a.rag_pt : 0;
+  const int64_t chunk_sz = (int64_t)a.n_cand * (n_full * a.cpt + ragp_full);
+  const int chunk = (int)(patch / chunk_sz);
+  const int crem = (int)(patch % chunk_sz);
+  const int cw = (a.npt - chunk * a.cpt) < a.cpt ? (a.npt - chunk * a.cpt) : a.cpt;
+  const int nfull_p = n_full * a.n_cand * cw;
+  if (crem < nfull_p) {
+    const int r2 = crem % (a.n_cand * cw);
+    cand = r2 / cw;
+    to = (crem / (a.n_cand * cw)) * PATCH_O + (slot % PATCH_O);
+    tt = (chunk * a.cpt + r2 % cw) * PATCH_T + (slot / PATCH_O);
+  } else {
+    const int ragp = (cw * PATCH_T + a.rag_pt - 1) / a.rag_pt;
+    const int r2 = crem - nfull_p, col = slot / a.rag;
+    cand = r2 / ragp;
+    if (col >= a.rag_pt) return false;
+    to = n_full * PATCH_O + (slot % a.rag);
+    tt = chunk * a.cpt * PATCH_T + (r2 % ragp) * a.rag_pt + col;
+    if (tt >= (chunk * a.cpt + cw) * PATCH_T) return false;
+  }
+  return to < a.tiles_o && tt < a.tiles_t;
+}
+
 template <typename T, int BO, int BT, int WO, int WT, int EPI>
 __global__ __launch_bounds__((BO / WO) * (BT / WT) * 64) void gemm_kernel(GemmDev a) {
   constexpr int NWO = BO / WO, NWT = BT / WT, NW = NWO * NWT, NT = NW * 64;
@@ -333,26 +374,8 @@ __global__ __launch_bounds__((BO / WO) * (BT / WT) * 64) void gemm_kernel(GemmDe
   __shared__ __attribute__((aligned(16))) unsigned char lds[2 * STAGE];
   __shared__ float red[NW];
 
-  // ---- tile of this block: patches of PATCH_O x PATCH_T tiles, one patch per
-  // XCD at a time (blocks are dealt to the 8 XCDs round-robin by block id).
-  const int64_t bid = blockIdx.x;
-  const int64_t round = bid / (8 * PATCH_O * PATCH_T);
-  const int within = (int)(bid % (8 * PATCH_O * PATCH_T));
-  const int64_t patch = round * 8 + (within & 7);
-  const int slot = within >> 3;
-  if (patch >= a.n_patches) return;
-  // Patch order: chunks of cpt token patches; inside a chunk every candidate and every
-  // output patch row is visited before the next chunk, so the chunk's tokens are served by
-  // the last-level cache instead of being streamed from HBM once per (candidate, row).
-  const int64_t chunk_sz = (int64_t)a.cpt * a.n_cand * a.npo;
-  const int chunk = (int)(patch / chunk_sz);
-  const int crem = (int)(patch % chunk_sz);
-  const int cw = (a.npt - chunk * a.cpt) < a.cpt ? (a.npt - chunk * a.cpt) : a.cpt;
-  const int cand = crem / (a.npo * cw);
-  const int prem = crem % (a.npo * cw);
-  const int to = (prem / cw) * PATCH_O + (slot % PATCH_O);
-  const int tt = (chunk * a.cpt + prem % cw) * PATCH_T + (slot / PATCH_O);
-  if (to >= a.tiles_o || tt >= a.tiles_t) return;
+  int cand, to, tt;
+  if (!decode_tile(a, blockIdx.x, cand, to, tt)) return;
   const int64_t o0 = (int64_t)to * BO, t0 = (int64_t)tt * BT;
 
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
@@ -512,6 +535,7 @@ __global__ __launch_bounds__(NWO * NWT * 64) void gemm_dma_kernel(GemmDev a) {
   constexpr int BO = 256, BT = 256, WO = BO / NWO, WT = BT / NWT, NW = NWO * NWT;
   constexpr int FA = WO / 32, FB = WT / 32, NF = FA + FB, KK = BK_ / 16;
   static_assert(NF == 6 || NF == 8, "fragment count");
+  static_assert(BK_ == 64, "the chunk swizzle below is written for 128-byte LDS rows");
   constexpr int RB = BK_ * 2;             // bytes per LDS row
   constexpr int CPR = BK_ / 8;            // 16-byte chunks per row
   constexpr int STAGE = (BO + BT) * RB;
@@ -522,24 +546,8 @@ __global__ __launch_bounds__(NWO * NWT * 64) void gemm_dma_kernel(GemmDev a) {
   __shared__ __attribute__((aligned(1024))) unsigned char lds[NSTAGE * STAGE];
   __shared__ float red[NW];
 
-  const int64_t bid = blockIdx.x;
-  const int64_t round = bid / (8 * PATCH_O * PATCH_T);
-  const int within = (int)(bid % (8 * PATCH_O * PATCH_T));
-  const int64_t patch = round * 8 + (within & 7);
-  const int slot = within >> 3;
-  if (patch >= a.n_patches) return;
-  // Patch order: chunks of cpt token patches; inside a chunk every candidate and every
-  // output patch row is visited before the next chunk, so the chunk's tokens are served by
-  // the last-level cache instead of being streamed from HBM once per (candidate, row).
-  const int64_t chunk_sz = (int64_t)a.cpt * a.n_cand * a.npo;
-  const int chunk = (int)(patch / chunk_sz);
-  const int crem = (int)(patch % chunk_sz);
-  const int cw = (a.npt - chunk * a.cpt) < a.cpt ? (a.npt - chunk * a.cpt) : a.cpt;
-  const int cand = crem / (a.npo * cw);
-  const int prem = crem % (a.npo * cw);
-  const int to = (prem / cw) * PATCH_O + (slot % PATCH_O);
-  const int tt = (chunk * a.cpt + prem % cw) * PATCH_T + (slot / PATCH_O);
-  if (to >= a.tiles_o || tt >= a.tiles_t) return;
+  int cand, to, tt;
+  if (!decode_tile(a, blockIdx.x, cand, to, tt)) return;
   const int64_t o0 = (int64_t)to * BO, t0 = (int64_t)tt * BT;
 
   const int tid = threadIdx.x, lane = tid & 63;
@@ -562,7 +570,7 @@ __global__ __launch_bounds__(NWO * NWT * 64) void gemm_dma_kernel(GemmDev a) {
   for (int j = 0; j < DPO; ++j) {
     const int r = (j * NW + wave) * RPD + lane / CPR;
     const int p = lane % CPR;
-    const int c = BK_ == 64 ? (p ^ ((r >> 1) & 7)) : (p ^ ((r >> 2) & 3));
+    const int c = p ^ ((r >> 1) & 7);
     voa[j] = r * (int)a.ldw * 2 + c * 16;
     vob[j] = r * (int)a.ldx * 2 + c * 16;
   }
@@ -594,7 +602,7 @@ __global__ __launch_bounds__(NWO * NWT * 64) void gemm_dma_kernel(GemmDev a) {
 #pragma unroll
   for (int kk = 0; kk < KK; ++kk) {
     const int c = kk * 2 + fhi;
-    const int p = BK_ == 64 ? (c ^ ((frow >> 1) & 7)) : (c ^ ((frow >> 2) & 3));
+    const int p = c ^ ((frow >> 1) & 7);
     const uint32_t o = (uint32_t)(frow * RB + p * 16);
     offA[kk] = lds0 + o + (wo * WO) * RB;
     offB[kk] = lds0 + o + BO * RB + (wt * WT) * RB;
@@ -701,16 +709,8 @@ __global__ __launch_bounds__(NWO * NWT * 64) void gemm_dma_kernel(GemmDev a) {
 // ---- host side ---------------------------------------------------------------
 constexpr int kBO = 256, kBT = 256, kWO = 128, kWT = 64;
 constexpr int64_t kChunkBytes = (int64_t)128 << 20;
-#ifndef TLQ_DMA_BK
-#define TLQ_DMA_BK 64
-#define TLQ_DMA_STAGES 2
-#endif
-#ifndef TLQ_DMA_NWO
-#define TLQ_DMA_NWO 2
-#define TLQ_DMA_NWT 4
-#endif
-constexpr int kDmaBK = TLQ_DMA_BK, kDmaStages = TLQ_DMA_STAGES;
-constexpr int kDmaNWO = TLQ_DMA_NWO, kDmaNWT = TLQ_DMA_NWT;
+constexpr int kDmaBK = 64, kDmaStages = 2;   // k-tile depth and LDS ring slots of the pipelined kernel
+constexpr int kDmaNWO = 2, kDmaNWT = 4;      // its 2 x 4 wave grid (128 x 64 outputs per wave)
 
 void gemm_tile_counts(int64_t n_tok, int64_t c_out, int64_t* tiles_o, int64_t* tiles_t) {
   *tiles_o = ceil_div(c_out, kBO);
@@ -730,12 +730,30 @@ static GemmDev make_dev(const GemmArgs& g) {
   gemm_tile_counts(g.n_tok, g.c_out, &to, &tt);
   d.tiles_o = (int)to; d.tiles_t = (int)tt;
   d.npo = (int)ceil_div(to, PATCH_O); d.npt = (int)ceil_div(tt, PATCH_T);
-  d.n_patches = (int64_t)g.n_cand * d.npo * d.npt;
-  // tokens of one chunk: at most kChunkBytes (half of the 256 MB last-level cache; measured
-  // best on 13B-class shapes, no effect while all tokens fit)
+  d.rag = (int)(to % PATCH_O);
+  d.rag_pt = d.rag == 0 ? PATCH_T : (d.rag == 3 ? 10 : (PATCH_O * PATCH_T) / d.rag);
+  // Tokens of one chunk.  While all tokens fit in half of the 256 MB last-level cache there is one
+  // chunk.  Otherwise a chunk holds the largest power-of-two number of token patches within that
+  // budget: with 1, 2, 4 or 8 patches per (candidate, patch row) the round-robin deal keeps every XCD
+  // on the same token patch from one candidate to the next, which measured steadier (and on most
+  // boxes faster) on 153,600-token inputs than 3, 5 or 6 patches, whose speed flips between
+  // launches by up to 8 %.
   const int64_t patch_bytes = (int64_t)PATCH_T * kBT * g.c_in * 2;
-  const int64_t c = kChunkBytes / patch_bytes;
-  d.cpt = c < 1 ? 1 : (c > d.npt ? d.npt : (int)c);
+  if ((int64_t)d.npt * patch_bytes <= kChunkBytes) {
+    d.cpt = d.npt;
+  } else {
+    d.cpt = 1;
+    while (d.cpt * 2 <= PATCH_T && (int64_t)d.cpt * 2 * patch_bytes <= kChunkBytes) d.cpt *= 2;
+  }
+  {
+    const int n_full = d.rag ? d.npo - 1 : d.npo;
+    const int64_t full_chunks = d.npt / d.cpt;
+    const int cw_last = d.npt % d.cpt;
+    auto per_cand = [&](int cw) {
+      return (int64_t)n_full * cw + (d.rag ? (cw * PATCH_T + d.rag_pt - 1) / d.rag_pt : 0);
+    };
+    d.n_patches = (int64_t)g.n_cand * (full_chunks * per_cand(d.cpt) + (cw_last ? per_cand(cw_last) : 0));
+  }
   return d;
 }
 
@@ -760,6 +778,33 @@ static hipError_t launch_gemm(const GemmArgs& g, const char* name, hipStream_t s
     else gemm_kernel<BF16, kBO, kBT, kWO, kWT, EPI><<<(unsigned)blocks, NT, 0, stream>>>(d);
   }
   return hipGetLastError();
+}
+
+// Host-side check of the block -> tile map for one problem shape: walks every block id of the
+// launch and counts how often each (candidate, tile) is produced.  Returns the number of tiles
+// that are not produced exactly once (0 = the map is a bijection onto the tiles), or -1 for an
+// invalid shape.  *blocks_out receives the grid size.
+int64_t tile_map_defects(int64_t n_tok, int64_t c_in, int64_t c_out, int n_cand, int64_t* blocks_out) {
+  if (n_tok <= 0 || c_in <= 0 || c_out <= 0 || n_cand <= 0) return -1;
+  GemmArgs g{};
+  g.n_tok = n_tok; g.c_in = c_in; g.c_out = c_out; g.n_cand = n_cand;
+  const GemmDev d = make_dev(g);
+  const int64_t blocks = ceil_div(d.n_patches, 8) * 8 * PATCH_O * PATCH_T;
+  if (blocks_out) *blocks_out = blocks;
+  const int64_t tiles = (int64_t)n_cand * d.tiles_o * d.tiles_t;
+  unsigned char* seen = (unsigned char*)calloc((size_t)tiles, 1);
+  if (!seen) return -1;
+  int64_t bad = 0;
+  for (int64_t b = 0; b < blocks; ++b) {
+    int cand, to, tt;
+    if (!decode_tile(d, b, cand, to, tt)) continue;
+    if (cand < 0 || cand >= n_cand || to < 0 || tt < 0) { ++bad; continue; }
+    unsigned char& c = seen[((int64_t)cand * d.tiles_o + to) * d.tiles_t + tt];
+    if (c < 255) ++c;
+  }
+  for (int64_t i = 0; i < tiles; ++i) bad += seen[i] != 1;
+  free(seen);
+  return bad;
 }
 
 hipError_t launch_gemm_loss(const GemmArgs& g, hipStream_t stream) {

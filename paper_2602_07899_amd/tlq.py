@@ -69,6 +69,7 @@ _SIGNATURES = {
     "tlq_causal_attention": (C.c_int, [_P, _I64, _P, _I64, _P, _I64, _I64, _I32, _I32, _I32, _PP, _P, _I64, _P]),
     "tlq_silu_mul": (C.c_int, [_P, _I64, _P, _I64, _I64, _I64, _PP, _P, _I64, _P]),
     "tlq_residual_add": (C.c_int, [_P, _I64, _P, _I64, _I64, _I64, _PP, _P, _I64, _P]),
+    "tlq_selftest_tile_map": (C.c_int64, [_I64, _I64, _I64, _I32, C.POINTER(C.c_int64)]),
     "tlq_profile_enable": (C.c_int, [C.c_int]),
     "tlq_profile_enabled": (C.c_int, []),
     "tlq_profile_reset": (C.c_int, []),
@@ -93,6 +94,13 @@ def lib():
             fn.restype, fn.argtypes = res, args
         _lib = l
     return _lib
+
+
+def selftest_tile_map(n_tok, c_in, c_out, n_cand):
+    """(defects, workgroups) of the contraction kernels' block -> tile map for one shape (host only)."""
+    blocks = C.c_int64(0)
+    bad = lib().tlq_selftest_tile_map(n_tok, c_in, c_out, n_cand, C.byref(blocks))
+    return int(bad), int(blocks.value)
 
 
 def status_string(status: int) -> str:

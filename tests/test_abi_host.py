@@ -136,3 +136,28 @@ def test_workspace_queries():
             >= tlq.apply_best_workspace_bytes(256, 512, 512, p) + 256 * 512 * 2)
     assert q(256, 512, 512, 20, pb) >= small + 256 * 512 * 2
     assert tlq.weighted_layer_err_workspace_bytes(256, 512, 512, p) >= 512 * 512 * 2
+
+
+@pytest.mark.parametrize("shape", [
+    (256, 512, 512, 20),            # small case: one tile column
+    (10240, 4096, 4096, 20),        # 7B attention linear: one token chunk
+    (10240, 4096, 11008, 20),       # 43 tile rows: last patch row has 3 (3 x 10 patches)
+    (10240, 11008, 4096, 20),       # deep linear: several token chunks of 2 patches, last of 1
+    (40960, 4096, 11008, 20),       # 160 tile columns in chunks of 4 patches
+    (153600, 5120, 13824, 20),      # 54 tile rows: last patch row has 2 (2 x 16 patches)
+    (153600, 13824, 5120, 20),
+    (700, 512, 300, 3), (5000, 1024, 1300, 2), (9000, 64, 2304, 1), (100000, 8192, 768, 2),
+    (257, 8, 257, 64), (1, 8, 1, 1), (70000, 2048, 256, 7),
+])
+def test_block_to_tile_map_covers_every_tile_once(shape):
+    """The contraction kernels derive (candidate, tile) from the block id alone; the host replay of
+    that map must hit every tile of every candidate exactly once, including the regrouped
+    incomplete patch row and a short last token chunk."""
+    n_tok, c_in, c_out, n_cand = shape
+    bad, blocks = tlq.selftest_tile_map(n_tok, c_in, c_out, n_cand)
+    tiles = n_cand * -(-n_tok // 256) * -(-c_out // 256)
+    assert bad == 0
+    assert blocks >= tiles and blocks % 256 == 0
+    if tiles >= 20000:
+        assert blocks <= 1.02 * tiles          # the regrouped patch row leaves < 2 % dead slots
+    assert tlq.selftest_tile_map(0, 8, 8, 1)[0] == -1
