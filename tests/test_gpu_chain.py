@@ -95,12 +95,16 @@ def test_chain_free_running(gpu):
             same_so_far = False
 
 
-def test_chain_full_size_7b_w3_properties(gpu):
+def test_chain_full_size_7b_w3(gpu):
     """The 7B-class chain at its real size (64 x 640 = 40,960 tokens, W3 g128, 20
-    alphas): too large for a full oracle, so what holds at any size is checked -
-    finite positive losses, first-minimum selection, unit scales at alpha = 0,
-    normalised exposed inputs, and the search's alpha = 0 loss equal to plain
-    round-to-nearest evaluated through the two single-purpose entry points."""
+    alphas).  A full oracle is out of reach, so (a) what holds at any size is checked -
+    finite positive losses, first-minimum selection, normalised exposed inputs, the
+    search's alpha = 0 loss equal to plain round-to-nearest evaluated through the two
+    single-purpose entry points - and (b) for two late linears (o_proj after three
+    quantised predecessors, down_proj at the end of the chain) the oracle evaluates 56
+    sampled tokens of the exposed input the chain actually produced: scale table from the
+    oracle's own statistic of that input, per-token errors of three candidates, and the
+    chain's recorded losses tied to the entry point that produced those errors."""
     import torch
     c = wl.CONFIGS["cfg3_7b_w3"]
     t = lambda a: torch.from_numpy(np.ascontiguousarray(a)).to(gpu)
@@ -138,3 +142,46 @@ def test_chain_full_size_7b_w3_properties(gpu):
     loss = torch.empty(1, dtype=torch.float32, device=gpu)
     tlq.weighted_layer_err(r["X"], wdq, None, Y, w, p, loss)
     assert loss.item() == r["losses"][0].item()
+    # (b) sampled-token parity against the oracle on the exposed inputs of o_proj and down_proj
+    wh = wl.make_token_weights(c, 0)
+    alh = wl.alpha_grid(c.n_alpha)
+    for li in (3, 6):
+        r, W = g[li], Ws[li]
+        Wh = W.cpu().numpy()
+        n_tok, c_in = r["X"].shape
+        xsum = np.zeros(c_in, np.float64)
+        for i in range(0, n_tok, 8192):       # the oracle's x_stat of the exposed input, streamed
+            xsum += np.abs(r["X"][i:i + 8192].cpu().numpy().astype(np.float64)).sum(axis=0)
+        ost = orc.scale_table((xsum / n_tok).astype(np.float32), alh)
+        st = torch.empty((c.n_alpha, c_in), dtype=torch.float32, device=gpu)
+        xs = torch.empty(c_in, dtype=torch.float32, device=gpu)
+        tlq.x_stat(r["X"], p, xs)
+        tlq.scale_table(xs, al, st)
+        ulp = np.abs(st.cpu().numpy().view(np.int32).astype(np.int64) - ost.view(np.int32))
+        assert ulp.max() <= 1, li
+        Y = torch.empty((n_tok, W.shape[0]), dtype=torch.float16, device=gpu)
+        tlq.ref_output(r["X"], W, Y, p)
+        rows = np.sort(np.random.default_rng(30 + li).choice(n_tok, 56, replace=False))
+        trows = torch.from_numpy(rows).to(gpu)
+        Xr, Yr = r["X"][trows].cpu().numpy(), Y[trows].cpu().numpy()
+        Yo = orc.ref_output(Xr, Wh)
+        assert np.all(np.abs(Yr.astype(np.float64) - Yo) <= 2.0 ** -10 * np.abs(Yo) + 1e-4), li
+        wdq = torch.empty_like(W)
+        pte = torch.empty(n_tok, dtype=torch.float32, device=gpu)
+        L = r["losses"].cpu().numpy().astype(np.float64)
+        bi = int(r["best_idx"].item())
+        for k in sorted({0, bi, 19}):
+            tlq.fake_quant(W, t(ost[k]), p, Wdq=wdq)
+            inv = (1.0 / ost[k].astype(np.float64)).astype(np.float32)
+            tlq.weighted_layer_err(r["X"], wdq, t(inv), Y, w, p, loss, pte)
+            _, _, _, deq = orc.fake_quant(Wh, ost[k], c.bits, c.group)
+            e = orc.per_token_err(Yr, orc.quantised_output(Xr, deq.astype(np.float16), inv_s=inv))
+            np.testing.assert_allclose(pte[trows].cpu().numpy(), e, rtol=1e-3)
+            e_pure = orc.per_token_err(Yr, orc.quantised_output(Xr, deq, s=ost[k]))
+            np.testing.assert_allclose(pte[trows].cpu().numpy(), e_pure, rtol=2e-3)
+            assert abs(loss.item() - L[k]) / L[k] < 2e-4, (li, k)
+        # the quantised output the chain propagated = f_q of the chosen scales on those rows
+        zo = orc.apply_best(Xr, Wh, r["best_scales"].cpu().numpy(), c.bits, c.group)
+        zg = r["Z"][trows].cpu().numpy().astype(np.float64)
+        assert np.all(np.abs(zg - zo) <= 2.0 ** -9 * np.abs(zo) + 2e-3 * np.abs(zo).mean()), li
+        print(f"linear {li}: sampled-token parity on the exposed input ok (best {bi})")

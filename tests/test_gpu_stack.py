@@ -249,6 +249,85 @@ def test_stack_full_size_block_properties(gpu):
     assert out["kernels"]["gemm_loss"]["launches"] == 7 and out["kernels"]["causal_attention"]["launches"] == 1
 
 
+def test_stack_full_size_block_sampled_parity(gpu):
+    """One block of the 13B-class stack at its full 153,600 tokens (bf16 activations, W3 g128, PassAct2)
+    with the oracle on sampled tokens of the exposed inputs the block actually produced.  For the
+    linears after the attention (o_proj) and at the end of the MLP (down_proj): the scale table
+    from the oracle's own statistic of the exposed input, the library's full-precision target
+    against the oracle's f_fp, per-token errors of three candidates from the full-size launch of
+    the single-candidate entry against the oracle, the recorded search losses tied to that entry,
+    and the complete 20-candidate oracle search on the sampled rows against the library's search
+    on the same rows."""
+    import torch
+    from paper_2602_07899_amd import run_stack
+    sw = wl.STACKS["cfg5_13b_stack"]
+    dt = torch.bfloat16
+    p = tlq.params(bits=3, group=sw.group, x_dtype=tlq.BF16, yref_dtype=tlq.BF16)
+    h0, w = run_stack.device_inputs(sw, gpu, dt)
+    al = torch.from_numpy(wl.alpha_grid(sw.n_alpha)).to(gpu)
+    alh = wl.alpha_grid(sw.n_alpha)
+    wfn = run_stack.device_weights(sw, gpu, dt)
+    Wl = dict(zip(gstack.LINEARS, wfn(0)))
+    kept = {}
+    out, hq, _ = gstack.run_stack(h0, lambda l: [Wl[n] for n in gstack.LINEARS], 1, w, al, p, sw.n_heads, sw.seq_len,
+                                  mode="passact2", keep=True)
+    torch.cuda.synchronize()
+    recs = out[0]
+    wh = w.cpu().numpy()
+    t32 = lambda a: torch.from_numpy(np.ascontiguousarray(a)).to(gpu)
+    for name in ("o_proj", "down_proj"):
+        r, W = recs[name], Wl[name]
+        X, Y = r["X"], r["Y_ref"]
+        n_tok, c_in = X.shape
+        Wh = W.float().cpu().numpy()
+        xsum = np.zeros(c_in, np.float64)
+        for i in range(0, n_tok, 8192):
+            xsum += np.abs(X[i:i + 8192].float().cpu().numpy().astype(np.float64)).sum(axis=0)
+        x_stat = (xsum / n_tok).astype(np.float32)
+        xs = torch.empty(c_in, dtype=torch.float32, device=gpu)
+        tlq.x_stat(X, p, xs)
+        assert np.array_equal(xs.cpu().numpy(), x_stat), name          # exact statistic of bf16 inputs
+        ost_ = orc.scale_table(x_stat, alh)
+        rows = np.sort(np.random.default_rng(len(name)).choice(n_tok, 56, replace=False))
+        trows = torch.from_numpy(rows).to(gpu)
+        Xr = X[trows].float().cpu().numpy()
+        Yr = Y[trows].float().cpu().numpy()
+        Yo = orc.ref_output(Xr, Wh)
+        assert np.all(np.abs(Yr.astype(np.float64) - Yo) <= 2.0 ** -8 * np.abs(Yo) + 2e-3 * np.abs(Yo).mean()), name
+        L = r["losses"].cpu().numpy().astype(np.float64)
+        bi = int(r["best_idx"].item())
+        assert np.all(np.isfinite(L)) and bi == int(np.argmin(L))
+        wdq = torch.empty_like(W)
+        loss = torch.empty(1, dtype=torch.float32, device=gpu)
+        pte = torch.empty(n_tok, dtype=torch.float32, device=gpu)
+        for k in sorted({0, bi, 19}):
+            tlq.fake_quant(W, t32(ost_[k]), p, Wdq=wdq)
+            inv = (1.0 / ost_[k].astype(np.float64)).astype(np.float32)
+            tlq.weighted_layer_err(X, wdq, t32(inv), Y, w, p, loss, pte)
+            _, _, _, deq = orc.fake_quant(Wh, ost_[k], 3, sw.group)
+            e = orc.per_token_err(Yr, orc.quantised_output(Xr, orc.round_to_bf16(deq), inv_s=inv))
+            np.testing.assert_allclose(pte[trows].cpu().numpy(), e, rtol=1e-3)
+            # the search folds the float dequantised weights; this entry takes them rounded to bf16,
+            # which moves the loss by about (2^-9 / relative quantisation error)^2
+            assert abs(loss.item() - L[k]) / L[k] < 3e-3, (name, k)
+        # the whole grid on the sampled rows: oracle search against the library's search
+        wr = (wh[rows] / wh[rows].sum()).astype(np.float32)
+        ref = orc.scale_search(Xr, Wh, Yr, wr, 3, sw.group, alh, x_stat=x_stat)
+        best = torch.empty(c_in, dtype=torch.float32, device=gpu)
+        idx = torch.empty(1, dtype=torch.int32, device=gpu)
+        ls = torch.empty(sw.n_alpha, dtype=torch.float32, device=gpu)
+        tlq.scale_search(X[trows].contiguous(), W, Y[trows].contiguous(), t32(wr), al, p, best, idx, ls, x_stat_in=xs)
+        rel = np.abs(ls.cpu().numpy().astype(np.float64) - ref["losses"]) / ref["losses"]
+        assert rel.max() < 1e-3, (name, rel.max())
+        srt = np.sort(ref["losses"])
+        assert int(idx.item()) == ref["best_idx"] or (srt[1] - srt[0]) / srt[0] < 1e-3
+        # what the block propagated is f_q of the chosen scales
+        zo = orc.apply_best(Xr, Wh, r["best_scales"].cpu().numpy(), 3, sw.group)
+        zg = r["Z"][trows].float().cpu().numpy().astype(np.float64)
+        assert np.all(np.abs(zg - zo) <= 2.0 ** -7 * np.abs(zo) + 4e-3 * np.abs(zo).mean()), name
+        print(f"{name}: best {bi}, sampled search max rel {rel.max():.2e}")
+
+
 def test_stack_with_topk_x_stat(gpu):
     """The paper's full recipe on the mini stack: x_stat = maximum over the Top-50 % positions by
     gradient norm (synthetic gradients), W4 per-channel symmetric, A8, PassAct2 - the GPU driver
