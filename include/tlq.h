@@ -202,6 +202,34 @@ tlq_status tlq_scale_search(const void* X, int64_t n_tok, int64_t c_in, int64_t 
                             float* s_table_out,
                             void* workspace, size_t workspace_bytes, void* stream);
 
+/* ---- tokens prepared once for several calls on the same X (Sec. 3.2.1: q/k/v and gate/up
+ * are searched, and then propagated, on one exposed input).  With x_dtype = BF16 and act_bits = 0
+ * every search and every propagation first re-expresses X in fp16 (see the conventions above);
+ * tlq_prepare_tokens does that once into a caller buffer of tlq_prepared_tokens_bytes bytes
+ * (256-byte aligned; 0 = these parameters need no preparation and `prepared` may be NULL), and
+ * the *_prepared variants below take that buffer instead of repeating the conversion.  They
+ * are otherwise identical to tlq_scale_search / tlq_apply_best (same arguments, same results
+ * bit for bit); prepared = NULL makes them the plain calls.  The buffer must have been
+ * filled from the same X, n_tok, c_in and parameters on the same stream order. */
+size_t tlq_prepared_tokens_bytes(int64_t n_tok, int64_t c_in, const tlq_params* p);
+tlq_status tlq_prepare_tokens(const void* X, int64_t n_tok, int64_t c_in, int64_t ldx,
+                              const tlq_params* p, void* prepared, size_t prepared_bytes,
+                              void* stream);
+tlq_status tlq_scale_search_prepared(const void* X, int64_t n_tok, int64_t c_in, int64_t ldx,
+                                     const void* W, int64_t c_out, int64_t ldw,
+                                     const void* Y_ref, int64_t ldy, const float* token_w,
+                                     const float* alpha_grid, int32_t n_alpha, const tlq_params* p,
+                                     const float* x_stat_in,
+                                     float* best_scales, int32_t* best_idx, float* losses,
+                                     float* s_table_out,
+                                     void* workspace, size_t workspace_bytes, void* stream,
+                                     const void* prepared);
+tlq_status tlq_apply_best_prepared(const void* X, int64_t n_tok, int64_t c_in, int64_t ldx,
+                                   const void* W, int64_t c_out, int64_t ldw, const float* s,
+                                   const tlq_params* p, void* X_next, int64_t ld_next,
+                                   void* workspace, size_t workspace_bytes, void* stream,
+                                   const void* prepared);
+
 /* ---- full-precision layer output (Sec. 3.2.1 f_fp without bias):
  * Y[t,o] = sum_c X[t,c] W[o,c], float accumulation, stored as yref_dtype. */
 tlq_status tlq_ref_output(const void* X, int64_t n_tok, int64_t c_in, int64_t ldx,

@@ -124,6 +124,14 @@ ErrPlan plan_err(void* ws, int64_t n_tok, int64_t c_in, int64_t c_out, bool bf16
   return e;
 }
 
+// Tokens re-expressed for the matrix cores (see launch_xprep), shared by several calls on one X:
+// [bits of max|X| : 256 bytes][X * 2^-shift as fp16, dense n_tok x c_in].
+struct Prepared { const uint32_t* xmax; const uint16_t* xh; };
+bool needs_prepared(const tlq_params* p) { return p->x_dtype == TLQ_BF16 && p->act_bits == 0; }
+Prepared view_prepared(const void* buf) {
+  return Prepared{(const uint32_t*)buf, (const uint16_t*)((const unsigned char*)buf + 256)};
+}
+
 }  // namespace
 
 extern "C" {
@@ -316,13 +324,13 @@ size_t tlq_scale_search_workspace_bytes(int64_t n_tok, int64_t c_in, int64_t c_o
                      use_diff_form(p, n_tok, c_out)).bytes;
 }
 
-tlq_status tlq_scale_search(const void* X, int64_t n_tok, int64_t c_in, int64_t ldx,
+static tlq_status scale_search_impl(const void* X, int64_t n_tok, int64_t c_in, int64_t ldx,
                             const void* W, int64_t c_out, int64_t ldw, const void* Y_ref,
                             int64_t ldy, const float* token_w, const float* alpha_grid,
                             int32_t n_alpha, const tlq_params* p, const float* x_stat_in,
                             float* best_scales, int32_t* best_idx, float* losses,
                             float* s_table_out, void* workspace, size_t workspace_bytes,
-                            void* stream) {
+                            void* stream, const void* prepared) {
   if (!X || !W || !Y_ref || !token_w || !alpha_grid || !best_scales || !best_idx || !losses)
     return TLQ_ERR_NULL;
   TLQ_TRY(check_params(p));
@@ -339,13 +347,19 @@ tlq_status tlq_scale_search(const void* X, int64_t n_tok, int64_t c_in, int64_t 
   const bool act = p->act_bits != 0;
   const bool diff = use_diff_form(p, n_tok, c_out);
   SearchPlan s = plan_search(workspace, n_tok, c_in, c_out, n_alpha, bf16, act, diff);
+  if (prepared && !aligned(prepared, 256)) return TLQ_ERR_ALIGN;
+  const bool use_prep = prepared && needs_prepared(p);
+  if (use_prep) {   // the caller's copy replaces the workspace one
+    const Prepared v = view_prepared(prepared);
+    s.xmax = const_cast<uint32_t*>(v.xmax); s.xh = const_cast<uint16_t*>(v.xh);
+  }
 
   const float* x_stat = x_stat_in;
   if (!x_stat) {  // S0
     TLQ_HIP(launch_xstat(X, n_tok, c_in, ldx, bf16, p->xstat_kind, s.xs_partial, s.x_stat, st));
     x_stat = s.x_stat;
   }
-  if (bf16 && !act) TLQ_HIP(launch_xprep(X, n_tok, c_in, ldx, s.xmax, s.xh, st));
+  if (bf16 && !act && !use_prep) TLQ_HIP(launch_xprep(X, n_tok, c_in, ldx, s.xmax, s.xh, st));
   // S1
   TLQ_HIP(launch_scale_table(x_stat, c_in, alpha_grid, n_alpha, s.s_table, s.inv_table,
                              (bf16 && !act) ? s.xmax : nullptr, st));
@@ -401,6 +415,51 @@ tlq_status tlq_scale_search(const void* X, int64_t n_tok, int64_t c_in, int64_t 
   return TLQ_OK;
 }
 
+tlq_status tlq_scale_search(const void* X, int64_t n_tok, int64_t c_in, int64_t ldx,
+                            const void* W, int64_t c_out, int64_t ldw, const void* Y_ref,
+                            int64_t ldy, const float* token_w, const float* alpha_grid,
+                            int32_t n_alpha, const tlq_params* p, const float* x_stat_in,
+                            float* best_scales, int32_t* best_idx, float* losses,
+                            float* s_table_out, void* workspace, size_t workspace_bytes,
+                            void* stream) {
+  return scale_search_impl(X, n_tok, c_in, ldx, W, c_out, ldw, Y_ref, ldy, token_w, alpha_grid, n_alpha, p,
+                           x_stat_in, best_scales, best_idx, losses, s_table_out, workspace, workspace_bytes,
+                           stream, nullptr);
+}
+
+tlq_status tlq_scale_search_prepared(const void* X, int64_t n_tok, int64_t c_in, int64_t ldx,
+                                     const void* W, int64_t c_out, int64_t ldw, const void* Y_ref,
+                                     int64_t ldy, const float* token_w, const float* alpha_grid,
+                                     int32_t n_alpha, const tlq_params* p, const float* x_stat_in,
+                                     float* best_scales, int32_t* best_idx, float* losses,
+                                     float* s_table_out, void* workspace, size_t workspace_bytes,
+                                     void* stream, const void* prepared) {
+  return scale_search_impl(X, n_tok, c_in, ldx, W, c_out, ldw, Y_ref, ldy, token_w, alpha_grid, n_alpha, p,
+                           x_stat_in, best_scales, best_idx, losses, s_table_out, workspace, workspace_bytes,
+                           stream, prepared);
+}
+
+// ------------------------------------------------ tokens prepared once for several calls
+size_t tlq_prepared_tokens_bytes(int64_t n_tok, int64_t c_in, const tlq_params* p) {
+  if (n_tok <= 0 || c_in <= 0 || check_params(p) != TLQ_OK || !needs_prepared(p)) return 0;
+  return 256 + align_up((size_t)n_tok * (size_t)c_in * 2, 256);
+}
+
+tlq_status tlq_prepare_tokens(const void* X, int64_t n_tok, int64_t c_in, int64_t ldx, const tlq_params* p,
+                              void* prepared, size_t prepared_bytes, void* stream) {
+  if (!X) return TLQ_ERR_NULL;
+  TLQ_TRY(check_params(p));
+  if (!dims_ok(n_tok, c_in, ldx) || (c_in % 8) != 0) return TLQ_ERR_SHAPE;
+  if (!mat16_aligned(X, ldx)) return TLQ_ERR_ALIGN;
+  const size_t need = tlq_prepared_tokens_bytes(n_tok, c_in, p);
+  if (need == 0) return TLQ_OK;                       // nothing to prepare for these parameters
+  if (!prepared || prepared_bytes < need) return TLQ_ERR_WORKSPACE;
+  if (!aligned(prepared, 256)) return TLQ_ERR_ALIGN;
+  const Prepared v = view_prepared(prepared);
+  return hip_status(launch_xprep(X, n_tok, c_in, ldx, const_cast<uint32_t*>(v.xmax), const_cast<uint16_t*>(v.xh),
+                                 (hipStream_t)stream));
+}
+
 // ---------------------------------------------------------------- f_fp output
 tlq_status tlq_ref_output(const void* X, int64_t n_tok, int64_t c_in, int64_t ldx,
                           const void* W, int64_t c_out, int64_t ldw, void* Y, int64_t ldy,
@@ -430,10 +489,10 @@ size_t tlq_apply_best_workspace_bytes(int64_t n_tok, int64_t c_in, int64_t c_out
          (p->act_bits != 0 ? align_up((size_t)n_tok * sizeof(float), 256) : 0);
 }
 
-tlq_status tlq_apply_best(const void* X, int64_t n_tok, int64_t c_in, int64_t ldx,
+static tlq_status apply_best_impl(const void* X, int64_t n_tok, int64_t c_in, int64_t ldx,
                           const void* W, int64_t c_out, int64_t ldw, const float* s,
                           const tlq_params* p, void* X_next, int64_t ld_next, void* workspace,
-                          size_t workspace_bytes, void* stream) {
+                          size_t workspace_bytes, void* stream, const void* prepared) {
   if (!X || !W || !s || !X_next) return TLQ_ERR_NULL;
   TLQ_TRY(check_params(p));
   if (!dims_ok(n_tok, c_in, ldx) || !dims_ok(c_out, c_in, ldw) || !dims_ok(n_tok, c_out, ld_next))
@@ -452,7 +511,13 @@ tlq_status tlq_apply_best(const void* X, int64_t n_tok, int64_t c_in, int64_t ld
   const bool act = p->act_bits != 0;
   uint16_t* xh = (bf16 || act) ? c.take<uint16_t>((size_t)n_tok * c_in) : nullptr;
   float* sig = act ? c.take<float>((size_t)n_tok) : nullptr;
-  if (bf16 && !act) TLQ_HIP(launch_xprep(X, n_tok, c_in, ldx, xmax, xh, st));
+  if (prepared && !aligned(prepared, 256)) return TLQ_ERR_ALIGN;
+  if (prepared && needs_prepared(p)) {
+    const Prepared v = view_prepared(prepared);
+    xmax = const_cast<uint32_t*>(v.xmax); xh = const_cast<uint16_t*>(v.xh);
+  } else if (bf16 && !act) {
+    TLQ_HIP(launch_xprep(X, n_tok, c_in, ldx, xmax, xh, st));
+  }
   TLQ_HIP(launch_recip(s, c_in, (bf16 && !act) ? xmax : nullptr, inv, st));
   if (act) TLQ_HIP(launch_act_quant(X, n_tok, c_in, ldx, bf16, inv, 0, 1, p->act_bits, xh, sig, nullptr, st));
   QuantArgs q{};
@@ -467,6 +532,22 @@ tlq_status tlq_apply_best(const void* X, int64_t n_tok, int64_t c_in, int64_t ld
   g.Wh = what; g.c_out = c_out; g.ldw = c_in; g.w_cand_stride = 0; g.n_cand = 1; g.bf16 = false;
   g.Yout = X_next; g.ldo = ld_next; g.yout_dtype = p->x_dtype;
   return hip_status(launch_gemm_store(g, st));
+}
+
+tlq_status tlq_apply_best(const void* X, int64_t n_tok, int64_t c_in, int64_t ldx,
+                          const void* W, int64_t c_out, int64_t ldw, const float* s,
+                          const tlq_params* p, void* X_next, int64_t ld_next, void* workspace,
+                          size_t workspace_bytes, void* stream) {
+  return apply_best_impl(X, n_tok, c_in, ldx, W, c_out, ldw, s, p, X_next, ld_next, workspace, workspace_bytes,
+                         stream, nullptr);
+}
+
+tlq_status tlq_apply_best_prepared(const void* X, int64_t n_tok, int64_t c_in, int64_t ldx,
+                                   const void* W, int64_t c_out, int64_t ldw, const float* s,
+                                   const tlq_params* p, void* X_next, int64_t ld_next, void* workspace,
+                                   size_t workspace_bytes, void* stream, const void* prepared) {
+  return apply_best_impl(X, n_tok, c_in, ldx, W, c_out, ldw, s, p, X_next, ld_next, workspace, workspace_bytes,
+                         stream, prepared);
 }
 
 // ------------------------------------------------------------ chain glue

@@ -97,7 +97,10 @@ def run(stack_name, bits, mode="passact2", joint=False, n_layers=None, n_samples
     layers = n_layers or sw.n_layers
     h0, w = device_inputs(sw, dev, dtype, n_samples)
     al = torch.from_numpy(wl.alpha_grid(sw.n_alpha)).to(dev)
-    journal = gstack.Journal(journal_path) if journal_path else None
+    jcfg = {"stack": stack_name, "seed": sw.seed, "bits": bits, "group": p.group, "symmetric": int(p.symmetric),
+            "act_bits": act_bits, "mode": mode, "joint": bool(joint), "x_stat": xstat, "xstat_kind": int(p.xstat_kind),
+            "n_samples": int(n_samples or sw.n_samples), "n_alpha": sw.n_alpha, "dtype": sw.act_dtype}
+    journal = gstack.Journal(journal_path, config=jcfg) if journal_path else None
     tlq.profile_reset()
     tlq.profile_enable(True)
     torch.cuda.synchronize()

@@ -30,11 +30,30 @@ GROUPS = (("q_proj", "k_proj", "v_proj"), ("o_proj",), ("gate_proj", "up_proj"),
 
 
 class Journal:
-    """Append-only JSON-lines record of finished searches, keyed by (layer, linear)."""
+    """Append-only JSON-lines record of finished searches, keyed by (layer, linear).  The first
+    line of the file is a header holding the run's configuration (quantiser, grid, propagation
+    mode, statistic, seed - whatever the caller passes as `config`); a journal whose header
+    differs from the current configuration belongs to another run and is refused."""
 
-    def __init__(self, path):
+    def __init__(self, path, config=None):
         self.path = path
         self.done = {}
+        self.config = config
+        self.header_written = False
+        if path and os.path.exists(path) and os.path.getsize(path) > 0:
+            with open(path, "rb") as f:
+                first = f.readline()
+            try:
+                head = json.loads(first.decode()) if first.endswith(b"\n") else None
+            except ValueError:
+                head = None
+            if isinstance(head, dict) and "journal_config" in head:
+                self.header_written = True
+                if config is not None and head["journal_config"] != config:
+                    raise ValueError(f"journal {path} was written with another configuration: "
+                                     f"{head['journal_config']} != {config}")
+            elif config is not None:
+                raise ValueError(f"journal {path} has no configuration header; refusing to resume from it")
         if path and os.path.exists(path):
             good = 0
             with open(path, "rb") as f:
@@ -46,7 +65,7 @@ class Journal:
                     if r is None and raw.strip():   # a line cut short by an interrupted run
                         break
                     good += len(raw)
-                    if r is not None:
+                    if r is not None and "journal_config" not in r:
                         self.done[(r["layer"], r["linear"])] = r
             if good != os.path.getsize(path):       # drop the damaged tail so that appends stay line-aligned
                 with open(path, "r+b") as f:
@@ -59,6 +78,9 @@ class Journal:
         self.done[(rec["layer"], rec["linear"])] = rec
         if self.path:
             with open(self.path, "a") as f:
+                if not self.header_written and self.config is not None:
+                    f.write(json.dumps({"journal_config": self.config}) + "\n")
+                    self.header_written = True
                 f.write(json.dumps(rec) + "\n")
                 f.flush()
                 os.fsync(f.fileno())
@@ -96,6 +118,13 @@ def run_stack(h0, weights_fn, n_layers, token_w, alpha_grid, p, n_heads, seq_len
             ws_cache["n"] = need
         return ws_cache["t"]
 
+    def prepared_buffer(nbytes):
+        if ws_cache.get("pn", 0) < nbytes:
+            ws_cache["p"] = None
+            ws_cache["p"] = torch.empty(nbytes, dtype=torch.uint8, device=dev)
+            ws_cache["pn"] = nbytes
+        return ws_cache["p"][:nbytes]
+
     def search_group(layer, names, Ws, Xq, Xfp, recs):
         """Returns (Zq list, Zfp list): per-member quantised and full-precision outputs
         (column slices of one matrix each)."""
@@ -107,7 +136,16 @@ def run_stack(h0, weights_fn, n_layers, token_w, alpha_grid, p, n_heads, seq_len
         for W, Yi in zip(Ws, Ys):
             tlq.ref_output(Xfp, W, Yi, p)
         Z = None if mode == "none" else new(tot)
+        # once per distinct exposed input: the channel statistic and (bf16) the fp16 re-expression
         xs_in = xstat_fn(layer, names, Xq) if xstat_fn is not None else None
+        if xs_in is None:
+            xs_in = torch.empty(c_in, dtype=torch.float32, device=dev)
+            tlq.x_stat(Xq, p, xs_in, workspace=workspace(c_in, max(widths)))
+        pb = tlq.prepared_tokens_bytes(n_tok, c_in, p)
+        prep = None
+        if pb:
+            prep = prepared_buffer(pb)
+            tlq.prepare_tokens(Xq, p, prep)
         units = [(names, torch.cat(Ws, dim=0) if len(Ws) > 1 else Ws[0], Y, Z)] if joint else \
                 [((n,), W, Yi, None if Z is None else Z[:, o:o + w]) for n, W, Yi, o, w in zip(names, Ws, Ys, offs, widths)]
         for unames, W, Yu, Zu in units:
@@ -116,17 +154,16 @@ def run_stack(h0, weights_fn, n_layers, token_w, alpha_grid, p, n_heads, seq_len
             idx = torch.empty(1, dtype=torch.int32, device=dev)
             losses = torch.empty(na, dtype=torch.float32, device=dev)
             old = journal.get(layer, unames[0]) if journal is not None else None
+            want_joint = list(unames) if len(unames) > 1 else None
+            if old is not None and (old.get("joint") != want_joint or not (0 <= old["best_idx"] < na)):
+                old = None      # recorded for another grouping, or no candidate was finite: search again
             if old is not None:                                   # resume: rebuild the chosen scales
-                xs = xs_in
-                if xs is None:
-                    xs = torch.empty(c_in, dtype=torch.float32, device=dev)
-                    tlq.x_stat(Xq, p, xs, workspace=ws)
-                tlq.scale_table(xs, alpha_grid[old["best_idx"]:old["best_idx"] + 1], best)
+                tlq.scale_table(xs_in, alpha_grid[old["best_idx"]:old["best_idx"] + 1], best)
                 idx.fill_(old["best_idx"])
                 losses.copy_(torch.tensor(old["losses"], dtype=torch.float32))
             else:
                 tlq.scale_search(Xq, W, Yu, token_w, alpha_grid, p, best, idx, losses, x_stat_in=xs_in,
-                                 workspace=ws)
+                                 workspace=ws, prepared=prep)
                 if journal is not None:
                     li, ll = int(idx.item()), [float(v) for v in losses.tolist()]
                     for n in unames:
@@ -134,7 +171,7 @@ def run_stack(h0, weights_fn, n_layers, token_w, alpha_grid, p, n_heads, seq_len
                                      "alpha": float(alpha_grid[li].item()) if li >= 0 else None, "losses": ll,
                                      "joint": list(unames) if len(unames) > 1 else None})
             if Zu is not None:
-                tlq.apply_best(Xq, W, best, p, Zu, workspace=ws)
+                tlq.apply_best(Xq, W, best, p, Zu, workspace=ws, prepared=prep)
             for n in unames:
                 rec = {"best_idx": idx, "losses": losses, "best_scales": best}
                 if keep:

@@ -62,6 +62,11 @@ _SIGNATURES = {
     "tlq_scale_search_workspace_bytes": (_SZ, [_I64, _I64, _I64, _I32, _PP]),
     "tlq_scale_search": (C.c_int, [_P, _I64, _I64, _I64, _P, _I64, _I64, _P, _I64, _P, _P, _I32,
                                    _PP, _P, _P, _P, _P, _P, _P, _SZ, _P]),
+    "tlq_prepared_tokens_bytes": (_SZ, [_I64, _I64, _PP]),
+    "tlq_prepare_tokens": (C.c_int, [_P, _I64, _I64, _I64, _PP, _P, _SZ, _P]),
+    "tlq_scale_search_prepared": (C.c_int, [_P, _I64, _I64, _I64, _P, _I64, _I64, _P, _I64, _P, _P, _I32,
+                                            _PP, _P, _P, _P, _P, _P, _P, _SZ, _P, _P]),
+    "tlq_apply_best_prepared": (C.c_int, [_P, _I64, _I64, _I64, _P, _I64, _I64, _P, _PP, _P, _I64, _P, _SZ, _P, _P]),
     "tlq_ref_output": (C.c_int, [_P, _I64, _I64, _I64, _P, _I64, _I64, _P, _I64, _PP, _P]),
     "tlq_apply_best_workspace_bytes": (_SZ, [_I64, _I64, _I64, _PP]),
     "tlq_apply_best": (C.c_int, [_P, _I64, _I64, _I64, _P, _I64, _I64, _P, _PP, _P, _I64, _P, _SZ, _P]),
@@ -217,17 +222,36 @@ def scale_search_workspace_bytes(n_tok, c_in, c_out, n_alpha, p):
     return lib().tlq_scale_search_workspace_bytes(n_tok, c_in, c_out, n_alpha, C.byref(p))
 
 
+def prepared_tokens_bytes(n_tok, c_in, p):
+    return lib().tlq_prepared_tokens_bytes(n_tok, c_in, C.byref(p))
+
+
+def prepare_tokens(X, p, prepared):
+    """Fill `prepared` (uint8 tensor of prepared_tokens_bytes bytes) from X; see tlq.h."""
+    n, ci = X.shape
+    _check(lib().tlq_prepare_tokens(_ptr(X), n, ci, _ld(X), C.byref(p), _ptr(prepared),
+                                    0 if prepared is None else prepared.numel(), _stream()), "tlq_prepare_tokens")
+    return prepared
+
+
 def scale_search(X, W, Y_ref, token_w, alpha_grid, p, best_scales, best_idx, losses,
-                 x_stat_in=None, s_table_out=None, workspace=None):
+                 x_stat_in=None, s_table_out=None, workspace=None, prepared=None):
     n, ci = X.shape
     co = W.shape[0]
     na = alpha_grid.numel()
     ws = workspace if workspace is not None else _ws(scale_search_workspace_bytes(n, ci, co, na, p), X)
-    _check(lib().tlq_scale_search(_ptr(X), n, ci, _ld(X), _ptr(W), co, _ld(W), _ptr(Y_ref),
-                                  _ld(Y_ref), _ptr(token_w), _ptr(alpha_grid), na, C.byref(p),
-                                  _ptr(x_stat_in), _ptr(best_scales), _ptr(best_idx), _ptr(losses),
-                                  _ptr(s_table_out), _ptr(ws), ws.numel(), _stream()),
-           "tlq_scale_search")
+    if prepared is None:
+        _check(lib().tlq_scale_search(_ptr(X), n, ci, _ld(X), _ptr(W), co, _ld(W), _ptr(Y_ref),
+                                      _ld(Y_ref), _ptr(token_w), _ptr(alpha_grid), na, C.byref(p),
+                                      _ptr(x_stat_in), _ptr(best_scales), _ptr(best_idx), _ptr(losses),
+                                      _ptr(s_table_out), _ptr(ws), ws.numel(), _stream()),
+               "tlq_scale_search")
+    else:
+        _check(lib().tlq_scale_search_prepared(_ptr(X), n, ci, _ld(X), _ptr(W), co, _ld(W), _ptr(Y_ref),
+                                               _ld(Y_ref), _ptr(token_w), _ptr(alpha_grid), na, C.byref(p),
+                                               _ptr(x_stat_in), _ptr(best_scales), _ptr(best_idx), _ptr(losses),
+                                               _ptr(s_table_out), _ptr(ws), ws.numel(), _stream(), _ptr(prepared)),
+               "tlq_scale_search_prepared")
 
 
 def ref_output(X, W, Y, p):
@@ -242,13 +266,18 @@ def apply_best_workspace_bytes(n_tok, c_in, c_out, p):
     return lib().tlq_apply_best_workspace_bytes(n_tok, c_in, c_out, C.byref(p))
 
 
-def apply_best(X, W, s, p, X_next, workspace=None):
+def apply_best(X, W, s, p, X_next, workspace=None, prepared=None):
     n, ci = X.shape
     co = W.shape[0]
     ws = workspace if workspace is not None else _ws(apply_best_workspace_bytes(n, ci, co, p), X)
-    _check(lib().tlq_apply_best(_ptr(X), n, ci, _ld(X), _ptr(W), co, _ld(W), _ptr(s), C.byref(p),
-                                _ptr(X_next), _ld(X_next), _ptr(ws), ws.numel(), _stream()),
-           "tlq_apply_best")
+    if prepared is None:
+        _check(lib().tlq_apply_best(_ptr(X), n, ci, _ld(X), _ptr(W), co, _ld(W), _ptr(s), C.byref(p),
+                                    _ptr(X_next), _ld(X_next), _ptr(ws), ws.numel(), _stream()),
+               "tlq_apply_best")
+    else:
+        _check(lib().tlq_apply_best_prepared(_ptr(X), n, ci, _ld(X), _ptr(W), co, _ld(W), _ptr(s), C.byref(p),
+                                             _ptr(X_next), _ld(X_next), _ptr(ws), ws.numel(), _stream(),
+                                             _ptr(prepared)), "tlq_apply_best_prepared")
     return X_next
 
 

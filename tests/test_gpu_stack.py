@@ -247,6 +247,46 @@ def test_stack_full_size_block_properties(gpu):
     q, k = np.asarray(blk["losses"][0]), np.asarray(blk["losses"][1])
     assert np.abs(q - k).max() < 0.02 * q.max()
     assert out["kernels"]["gemm_loss"]["launches"] == 7 and out["kernels"]["causal_attention"]["launches"] == 1
+    # once per distinct exposed input (4 per block), not once per search and per propagation
+    assert out["kernels"]["xstat_partial"]["launches"] == 4 and out["kernels"]["bf16_to_f16"]["launches"] == 4
+
+
+def test_prepared_tokens_variants_are_bit_identical(gpu):
+    """tlq_prepare_tokens + the *_prepared entry points against the plain calls (bf16 inputs): the shared
+    fp16 re-expression of X must change nothing, for the search and for the propagation; with fp16 inputs
+    nothing needs preparing and the query says so."""
+    import torch
+    g = np.random.default_rng(5)
+    n, ci, co = 700, 768, 520
+    X = dev(g.standard_normal((n, ci)) * np.where(g.random(ci) < 0.02, 300.0, 1.0), gpu, True)
+    W = dev(g.standard_normal((co, ci)) * 0.03, gpu, True)
+    w = g.lognormal(0, 1, n)
+    w = torch.from_numpy((w / w.sum()).astype(np.float32)).to(gpu)
+    al = torch.from_numpy(wl.alpha_grid(7)).to(gpu)
+    p = tlq.params(bits=4, group=128, x_dtype=tlq.BF16, yref_dtype=tlq.BF16)
+    Y = torch.empty((n, co), dtype=torch.bfloat16, device=gpu)
+    tlq.ref_output(X, W, Y, p)
+    nb = tlq.prepared_tokens_bytes(n, ci, p)
+    assert nb == 256 + n * ci * 2
+    assert tlq.prepared_tokens_bytes(n, ci, tlq.params()) == 0                      # fp16: nothing to prepare
+    assert tlq.prepared_tokens_bytes(n, ci, tlq.params(x_dtype=tlq.BF16, act_bits=8)) == 0
+    prep = torch.empty(nb, dtype=torch.uint8, device=gpu)
+    tlq.prepare_tokens(X, p, prep)
+    res = []
+    for pr in (None, prep):
+        best = torch.empty(ci, dtype=torch.float32, device=gpu)
+        idx = torch.empty(1, dtype=torch.int32, device=gpu)
+        ls = torch.empty(7, dtype=torch.float32, device=gpu)
+        tlq.scale_search(X, W, Y, w, al, p, best, idx, ls, prepared=pr)
+        Z = torch.empty((n, co), dtype=torch.bfloat16, device=gpu)
+        tlq.apply_best(X, W, best, p, Z, prepared=pr)
+        res.append((best, idx, ls, Z))
+    torch.cuda.synchronize()
+    for a, b in zip(*res):
+        assert torch.equal(a, b)
+    with pytest.raises(tlq.TlqError) as e:
+        tlq.prepare_tokens(X, p, prep[:1024])
+    assert e.value.status == tlq.ERR_WORKSPACE
 
 
 def test_stack_full_size_block_sampled_parity(gpu):
