@@ -26,13 +26,22 @@
  *     synchronises with the host or copies to the host.  Outputs are device
  *     resident and valid once the stream reaches the end of the call.
  *   - The return value reports argument validation and launch errors only.
- *     On any status other than TLQ_OK nothing was written.
+ *     Validation (every status except TLQ_ERR_LAUNCH) happens before any HIP call:
+ *     nothing was launched and nothing was written.  TLQ_ERR_LAUNCH means the HIP
+ *     runtime refused a launch part-way through the call: kernels enqueued before it
+ *     may still run and the outputs and the workspace must be treated as undefined.
+ *     Faults inside a kernel surface at the caller's next synchronisation.
  *   - Matrices are row-major with a row stride (`ld*`) in ELEMENTS.  16-bit
  *     matrices need 16-byte aligned base pointers and strides that are
  *     multiples of 8; otherwise TLQ_ERR_ALIGN.  c_in must be a multiple of 8
  *     and of `group` (TLQ_ERR_SHAPE otherwise).
  *   - Calls on different streams may run concurrently if their workspaces and
- *     outputs are disjoint.
+ *     outputs are disjoint.  The library keeps no state between calls except (a) the
+ *     optional per-kernel timing (tlq_profile_*: one process-wide table behind a mutex)
+ *     and (b) the fixed scratch array of tlq_x_stat_static.
+ *   - Float vectors that are read 16 bytes at a time (`s` of tlq_fake_quant and
+ *     tlq_apply_best) must be 16-byte aligned; `group` must be 0 or a multiple of 8
+ *     (TLQ_ERR_UNSUPPORTED otherwise); uint8 code matrices must be 8-byte aligned.
  *   - act_bits > 0 (Sec. 3.2.1 f_q with Q_a; quantiser of Sec. 2.2 per token row):
  *     xt = x * float(1/s); sigma_t = max(max_c |xt|, 1e-5) / (2^(n-1)-1);
  *     code = clip(rint(xt/sigma_t), -2^(n-1), 2^(n-1)-1); f_q = sigma_t * code . deq^T.

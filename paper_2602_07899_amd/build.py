@@ -37,8 +37,8 @@ def hipcc() -> str:
     return exe
 
 
-def _compile(src: str, extra=()):
-    obj = os.path.join(OBJ, src.replace(".hip", ".o"))
+def _compile(src: str, extra=(), suffix=""):
+    obj = os.path.join(OBJ, src.replace(".hip", suffix + ".o"))
     cmd = [hipcc(), *COMMON, *PER_FILE.get(src, []), *extra, "-c", os.path.join(CSRC, src), "-o", obj]
     r = subprocess.run(cmd, capture_output=True, text=True)
     msgs = "\n".join(l for l in (r.stdout + r.stderr).splitlines()
@@ -48,10 +48,10 @@ def _compile(src: str, extra=()):
     return obj, msgs
 
 
-def build(verbose: bool = True, extra=()) -> str:
+def build(verbose: bool = True) -> str:
     os.makedirs(OBJ, exist_ok=True)
     with cf.ThreadPoolExecutor(max_workers=min(8, len(SOURCES))) as ex:
-        results = list(ex.map(lambda s: _compile(s, extra), SOURCES))
+        results = list(ex.map(_compile, SOURCES))
     objs = [o for o, _ in results]
     if verbose:
         for (_, m), s in zip(results, SOURCES):
@@ -73,5 +73,33 @@ def build(verbose: bool = True, extra=()) -> str:
     return LIB
 
 
+# Host code of the argument-validation layer under AddressSanitizer + UndefinedBehaviorSanitizer.
+# Only the host pass of the three translation units without kernels of their own logic on the
+# validation paths is instrumented (device code cannot be sanitised here); the kernels' objects
+# are reused from the normal build.  The result is a driver executable that calls every entry
+# point with arguments that must be rejected before anything is launched, so it runs without a GPU.
+SANITIZED = ["api.hip", "noalloc.hip", "profile.hip"]
+SAN_FLAGS = ["-g", "-O1", "-Xarch_host", "-fsanitize=address", "-Xarch_host", "-fsanitize=undefined",
+             "-Xarch_host", "-fno-sanitize-recover=undefined", "-Xarch_host", "-fno-omit-frame-pointer"]
+
+
+def build_sanitized_driver() -> str:
+    """Build (and return the path of) the sanitizer driver; needs a finished normal build."""
+    plain = [os.path.join(OBJ, s.replace(".hip", ".o")) for s in SOURCES if s not in SANITIZED]
+    if not all(os.path.exists(o) for o in plain):
+        build(verbose=False)
+    with cf.ThreadPoolExecutor(max_workers=len(SANITIZED)) as ex:
+        san = [o for o, _ in ex.map(lambda s: _compile(s, SAN_FLAGS, "_san"), SANITIZED)]
+    exe = os.path.join(OBJ, "abi_validation_driver")
+    src = os.path.join(ROOT, "tests", "native", "abi_validation_driver.cpp")
+    cmd = [hipcc(), "--offload-arch=gfx950", "-std=c++17", "-g", "-O1", "-fsanitize=address", "-fsanitize=undefined",
+           "-fno-sanitize-recover=undefined", "-fno-gpu-sanitize", "-I", os.path.join(ROOT, "include"),
+           "-x", "c++", src, "-x", "none", *san, *plain, "-o", exe]
+    r = subprocess.run(cmd, capture_output=True, text=True)
+    if r.returncode != 0:
+        raise RuntimeError("sanitizer driver build failed:\n" + r.stdout + r.stderr)
+    return exe
+
+
 if __name__ == "__main__":
-    build(extra=sys.argv[1:])
+    build()

@@ -44,6 +44,7 @@ struct ProfScope {
   ~ProfScope();
   int slot;
   hipStream_t stream;
+  unsigned generation;
 };
 
 // ---- kernel launchers (each enqueues on `stream`, returns hipGetLastError) --

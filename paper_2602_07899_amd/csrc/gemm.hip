@@ -178,6 +178,10 @@ __device__ __forceinline__ void loss_rows_lds(const GemmDev& a, f32x16 (&acc)[FA
       *reinterpret_cast<uint4*>(ylds + row * (WO * 2) + ((cc ^ (row & 15)) << 4)) = v[j];
     }
   }
+  // the values are picked up by OTHER lanes of this wave: order the LDS writes before the reads
+  __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+  __builtin_amdgcn_wave_barrier();
+  __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
 #pragma unroll
   for (int j = 0; j < FB; ++j) {
     const int tok = j * 32 + frow;
@@ -230,6 +234,10 @@ __device__ __forceinline__ void store_rows_lds(const GemmDev& a, f32x16 (&acc)[F
   }
   uint16_t* Y = (uint16_t*)a.Yout;
   const int cr = lane / CPR, cc = lane % CPR;
+  // whole lines are read back by OTHER lanes of this wave: order the LDS writes before the reads
+  __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+  __builtin_amdgcn_wave_barrier();
+  __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
 #pragma unroll
   for (int j = 0; j < WT / RPI; ++j) {
     const int row = j * RPI + cr;

@@ -11,6 +11,9 @@ namespace tlq {
 namespace {
 
 struct Rec { int name_id; hipEvent_t start, stop; double work; };
+// every tlq_profile_collect / reset starts a new generation: a scope that was opened before
+// it must not touch the record list that was rebuilt in between
+unsigned g_generation = 0;
 struct Total { std::string name; int64_t launches; double ms; double work; };
 
 std::mutex g_mu;
@@ -35,7 +38,7 @@ hipEvent_t get_event_locked() {
 
 }  // namespace
 
-ProfScope::ProfScope(const char* name, hipStream_t s, double work) : slot(-1), stream(s) {
+ProfScope::ProfScope(const char* name, hipStream_t s, double work) : slot(-1), stream(s), generation(0) {
   std::lock_guard<std::mutex> lk(g_mu);
   if (!g_on) return;
   Rec r;
@@ -43,16 +46,21 @@ ProfScope::ProfScope(const char* name, hipStream_t s, double work) : slot(-1), s
   r.start = get_event_locked();
   r.stop = get_event_locked();
   r.work = work;
-  if (!r.start || !r.stop) return;
+  if (!r.start || !r.stop) {          // hand back whichever event was obtained
+    if (r.start) g_free.push_back(r.start);
+    if (r.stop) g_free.push_back(r.stop);
+    return;
+  }
   (void)hipEventRecord(r.start, stream);
   g_recs.push_back(r);
   slot = (int)g_recs.size() - 1;
+  generation = g_generation;
 }
 
 ProfScope::~ProfScope() {
   if (slot < 0) return;
   std::lock_guard<std::mutex> lk(g_mu);
-  if (slot < (int)g_recs.size()) (void)hipEventRecord(g_recs[slot].stop, stream);
+  if (generation == g_generation && slot < (int)g_recs.size()) (void)hipEventRecord(g_recs[slot].stop, stream);
 }
 
 }  // namespace tlq
@@ -85,6 +93,7 @@ tlq_status tlq_profile_collect(void) {
     g_free.push_back(r.stop);
   }
   g_recs.clear();
+  ++g_generation;
   return TLQ_OK;
 }
 
