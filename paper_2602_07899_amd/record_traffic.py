@@ -53,7 +53,7 @@ def main(prof_dir):
                     cur = {"cal": v, "gemm": []}
                     blocks.append(cur)
                 continue
-            if cur is not None and "gemm_dma_kernel" in k and k.rstrip().endswith(", 0>"):
+            if cur is not None and "gemm_dma_kernel" in k and ", 0>(" in k:
                 cur["gemm"].append(v)
         return blocks
 
