@@ -422,6 +422,30 @@ def test_full_size_7b_linear_sampled_parity(gpu, li):
     assert np.all(np.isfinite(losses)) and np.all(losses > 0) and idx == int(np.argmin(losses))
 
 
+@pytest.mark.parametrize("n,ci,co", [(700, 256, 1100),     # 5 tile rows: one full patch row + a 1 x 32 regrouped row
+                                     (2300, 128, 1300),    # 6 tile rows: 2 x 16 regrouped row; 9 tile columns
+                                     (520, 256, 1800),     # 8 tile rows (last one partial): no regrouping
+                                     (300, 128, 2900)])    # 12 tile rows -> 3 patch rows, last tile row partial
+def test_scale_search_with_several_patch_rows(gpu, n, ci, co):
+    """Outputs wide enough for several patch rows and an incomplete last one (the block -> tile map
+    regroups it), with ragged tokens and output rows: every candidate's loss against the full oracle."""
+    rng = np.random.default_rng(n + co)
+    X = rng.standard_normal((n, ci)).astype(np.float32)
+    X[:, rng.choice(ci, 3, replace=False)] *= 12.0
+    W = (rng.standard_normal((co, ci)) * 0.03).astype(np.float32)
+    X, W = X.astype(np.float16), W.astype(np.float16)
+    w = rng.lognormal(0, 1, n)
+    w = (w / w.sum()).astype(np.float32)
+    al = wl.alpha_grid(5)
+    Y = orc.ref_output(X, W).astype(np.float16)
+    p = tlq.params(bits=4, group=128)
+    best, idx, losses, st = run_search(gpu, X, W, Y, w, al, p)
+    ref = orc.scale_search(X, W, Y, w, 4, 128, al, s_table=st)
+    worst = check_losses(losses, ref["losses"], idx, f"{n}x{ci}x{co}")
+    assert worst < 3e-4
+    assert np.array_equal(best, ref["best_scales"]) or idx != ref["best_idx"]
+
+
 @pytest.mark.parametrize("li", [0, 4, 6])
 def test_full_size_13b_linear_sampled_parity(gpu, li):
     """q_proj (5120 x 5120), gate_proj (13824 x 5120: 54 tile rows, regrouped last patch row, token
