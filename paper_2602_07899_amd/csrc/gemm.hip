@@ -45,6 +45,53 @@ template <> struct Mma<BF16> {
   }
 };
 
+typedef float f32x4 __attribute__((ext_vector_type(4)));
+// 16x16x32: half the accumulator registers read and written per flop of the 32x32x16 shape.  The
+// matrix cores are power-limited with real operands, and a register-only loop with random operands
+// sustains 1840 TFLOP/s with this shape against 1585 with 32x32x16, so the pipelined kernel uses it.
+template <typename T> struct Mma16;
+template <> struct Mma16<F16> {
+  static __device__ __forceinline__ f32x4 run(const uint4& a, const uint4& b, const f32x4& c) {
+    return __builtin_amdgcn_mfma_f32_16x16x32_f16(__builtin_bit_cast(f16x8, a),
+                                                  __builtin_bit_cast(f16x8, b), c, 0, 0, 0);
+  }
+};
+template <> struct Mma16<BF16> {
+  static __device__ __forceinline__ f32x4 run(const uint4& a, const uint4& b, const f32x4& c) {
+    return __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, a),
+                                                   __builtin_bit_cast(bf16x8, b), c, 0, 0, 0);
+  }
+};
+
+// How a wave's accumulators map to (output row, token).  With either MFMA shape (weights as the
+// "A" operand, tokens as "B") a lane owns ONE token column per accumulator tile and groups of four
+// consecutive output rows ("quads").  A layout names its quads q < NQ and token blocks tb < NTB:
+//   tok(tb, lane)  token of the lane inside the wave tile,
+//   row(q, lane)   first of the four output rows of quad q inside the wave tile,
+//   get(acc, q, tb, r)  the accumulator of row(q) + r and tok(tb),
+//   tok_sum(v)     sum of v over the lanes that hold the same token.
+template <int FA, int FB> struct Acc32 {   // acc[FA][FB] of f32x16 (32x32x16)
+  static constexpr int NQ = FA * 4, NTB = FB, WO = FA * 32, WT = FB * 32;
+  static __device__ __forceinline__ int tok(int tb, int lane) { return tb * 32 + (lane & 31); }
+  static __device__ __forceinline__ int row(int q, int lane) { return (q >> 2) * 32 + (q & 3) * 8 + (lane >> 5) * 4; }
+  template <typename A> static __device__ __forceinline__ float get(const A& acc, int q, int tb, int r) {
+    return acc[q >> 2][tb][(q & 3) * 4 + r];
+  }
+  static __device__ __forceinline__ float tok_sum(float v) { return v + __shfl_xor(v, 32, 64); }
+};
+template <int IA, int JB> struct Acc16 {   // acc[IA][JB] of f32x4 (16x16x32)
+  static constexpr int NQ = IA, NTB = JB, WO = IA * 16, WT = JB * 16;
+  static __device__ __forceinline__ int tok(int tb, int lane) { return tb * 16 + (lane & 15); }
+  static __device__ __forceinline__ int row(int q, int lane) { return q * 16 + (lane >> 4) * 4; }
+  template <typename A> static __device__ __forceinline__ float get(const A& acc, int q, int tb, int r) {
+    return acc[q][tb][r];
+  }
+  static __device__ __forceinline__ float tok_sum(float v) {
+    v += __shfl_xor(v, 16, 64);
+    return v + __shfl_xor(v, 32, 64);
+  }
+};
+
 enum { EPI_LOSS = 0, EPI_LOSS_TOK = 1, EPI_STORE = 2 };
 constexpr int BK = 64;        // halves per k-tile
 constexpr int ROWB = BK * 2;  // bytes per LDS row
@@ -106,45 +153,44 @@ __device__ __forceinline__ void store_y1(void* Y, int odt, int64_t idx, float y)
 
 
 // Per-lane part of the loss of one wave tile whose first output row is `ow` and first
-// token is `tw`: sq[j] = sum over this lane's rows of (Y_ref - acc)^2 for its token of
-// fragment column j; part = sum_j token_w * sq[j].  YDT >= 0 fixes the Y_ref type at
+// token is `tw`: sq[tb] = sum over this lane's rows of (Y_ref - acc)^2 for its token of
+// token block tb; part = sum_tb token_w * sq[tb].  YDT >= 0 fixes the Y_ref type at
 // compile time; FULL promises that the whole wave tile lies inside the matrix.
-template <int YDT, bool FULL, int FA, int FB>
-__device__ __forceinline__ void loss_rows(const GemmDev& a, f32x16 (&acc)[FA][FB], const float* tsc,
-                                          int64_t ow, int64_t tw, float (&sq)[FB], float& part) {
-  const int lane = threadIdx.x & 63, frow = lane & 31, fhi = lane >> 5;
+template <int YDT, bool FULL, typename L, typename Acc>
+__device__ __forceinline__ void loss_rows(const GemmDev& a, const Acc& acc, const float* tsc,
+                                          int64_t ow, int64_t tw, float (&sq)[L::NTB], float& part) {
+  const int lane = threadIdx.x & 63;
   const int ydt = YDT >= 0 ? YDT : a.ydt;
 #pragma unroll
-  for (int j = 0; j < FB; ++j) {
-    const int64_t t = tw + j * 32 + frow;
+  for (int tb = 0; tb < L::NTB; ++tb) {
+    const int64_t t = tw + L::tok(tb, lane);
     float sumsq = 0.0f;
     if (FULL || t < a.n_tok) {
       // residual = y - sg * acc as one fused multiply-add; sg = 1 gives y - acc exactly
       const float nsg = tsc ? -tsc[t] : -1.0f;
 #pragma unroll
-      for (int i = 0; i < FA; ++i)
+      for (int q = 0; q < L::NQ; ++q) {
+        const int64_t o = ow + L::row(q, lane);
+        if (FULL || o + 3 < a.c_out) {
+          float y[4];
+          load_y4(a.Yref, ydt, t * a.ldy + o, y);
 #pragma unroll
-        for (int q = 0; q < 4; ++q) {
-          const int64_t o = ow + i * 32 + q * 8 + fhi * 4;
-          if (FULL || o + 3 < a.c_out) {
-            float y[4];
-            load_y4(a.Yref, ydt, t * a.ldy + o, y);
+          for (int r = 0; r < 4; ++r) {
+            const float d = __builtin_fmaf(nsg, L::get(acc, q, tb, r), y[r]);
+            sumsq += d * d;
+          }
+        } else {
 #pragma unroll
-            for (int r = 0; r < 4; ++r) {
-              const float d = __builtin_fmaf(nsg, acc[i][j][q * 4 + r], y[r]);
+          for (int r = 0; r < 4; ++r)
+            if (o + r < a.c_out) {
+              const float d = __builtin_fmaf(nsg, L::get(acc, q, tb, r), load_y(a.Yref, ydt, t * a.ldy + o + r));
               sumsq += d * d;
             }
-          } else {
-            for (int r = 0; r < 4; ++r)
-              if (o + r < a.c_out) {
-                const float d = __builtin_fmaf(nsg, acc[i][j][q * 4 + r], load_y(a.Yref, ydt, t * a.ldy + o + r));
-                sumsq += d * d;
-              }
-          }
         }
+      }
       part += a.token_w[t] * sumsq;
     }
-    sq[j] = sumsq;
+    sq[tb] = sumsq;
   }
 }
 
@@ -152,17 +198,17 @@ __device__ __forceinline__ void loss_rows(const GemmDev& a, f32x16 (&acc)[FA][FB
 // LDS: the wave copies its 64-token x 128-row piece with whole-line loads (each 128-byte line
 // is fetched once, 8 lines per instruction) into `ylds` (WT x WO 16-bit, this wave's own),
 // then every lane picks its values from there.  Reading Y_ref straight from the accumulator
-// layout touches 32 lines per instruction and each line 8 times.  16-byte chunks of a token
+// layout touches 16 or 32 lines per instruction and each line 8 times.  16-byte chunks of a token
 // row are stored at chunk ^ (token % 16), which makes the 8-byte reads conflict-free.
-template <typename YT, int FA, int FB>
-__device__ __forceinline__ void loss_rows_lds(const GemmDev& a, f32x16 (&acc)[FA][FB], const float* tsc,
-                                              int64_t ow, int64_t tw, float (&sq)[FB], float& part,
+template <typename YT, typename L, typename Acc>
+__device__ __forceinline__ void loss_rows_lds(const GemmDev& a, const Acc& acc, const float* tsc,
+                                              int64_t ow, int64_t tw, float (&sq)[L::NTB], float& part,
                                               unsigned char* ylds) {
-  constexpr int WO = FA * 32, WT = FB * 32;
+  constexpr int WO = L::WO, WT = L::WT;
   constexpr int CPR = WO / 8;              // 16-byte chunks per token row
   constexpr int RPI = 64 / CPR;            // token rows per wave-wide copy
   static_assert(CPR == 16 && WT % RPI == 0, "copy shape");
-  const int lane = threadIdx.x & 63, frow = lane & 31, fhi = lane >> 5;
+  const int lane = threadIdx.x & 63;
   const uint16_t* Y = (const uint16_t*)a.Yref;
   {
     const int cr = lane / CPR, cc = lane % CPR;
@@ -183,54 +229,52 @@ __device__ __forceinline__ void loss_rows_lds(const GemmDev& a, f32x16 (&acc)[FA
   __builtin_amdgcn_wave_barrier();
   __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
 #pragma unroll
-  for (int j = 0; j < FB; ++j) {
-    const int tok = j * 32 + frow;
+  for (int tb = 0; tb < L::NTB; ++tb) {
+    const int tok = L::tok(tb, lane);
     const int64_t t = tw + tok;
     const float nsg = tsc ? -tsc[t] : -1.0f;
     float sumsq = 0.0f;
 #pragma unroll
-    for (int i = 0; i < FA; ++i)
+    for (int q = 0; q < L::NQ; ++q) {
+      const int o = L::row(q, lane);        // multiple of 4: chunk o / 8, half (o / 4) % 2
+      const uint2 u = *reinterpret_cast<const uint2*>(ylds + tok * (WO * 2) + (((o >> 3) ^ (tok & 15)) << 4) +
+                                                      ((o >> 2) & 1) * 8);
+      const float y[4] = {YT::to_float((uint16_t)(u.x & 0xffffu)), YT::to_float((uint16_t)(u.x >> 16)),
+                          YT::to_float((uint16_t)(u.y & 0xffffu)), YT::to_float((uint16_t)(u.y >> 16))};
 #pragma unroll
-      for (int q = 0; q < 4; ++q) {
-        const uint2 u = *reinterpret_cast<const uint2*>(ylds + tok * (WO * 2) +
-                                                        (((i * 4 + q) ^ (tok & 15)) << 4) + fhi * 8);
-        const float y[4] = {YT::to_float((uint16_t)(u.x & 0xffffu)), YT::to_float((uint16_t)(u.x >> 16)),
-                            YT::to_float((uint16_t)(u.y & 0xffffu)), YT::to_float((uint16_t)(u.y >> 16))};
-#pragma unroll
-        for (int r = 0; r < 4; ++r) {
-          const float d = __builtin_fmaf(nsg, acc[i][j][q * 4 + r], y[r]);
-          sumsq += d * d;
-        }
+      for (int r = 0; r < 4; ++r) {
+        const float d = __builtin_fmaf(nsg, L::get(acc, q, tb, r), y[r]);
+        sumsq += d * d;
       }
+    }
     part += a.token_w[t] * sumsq;
-    sq[j] = sumsq;
+    sq[tb] = sumsq;
   }
 }
 
 // Store epilogue of an interior wave tile with a 16-bit output, through LDS: every lane drops
 // its rounded values into `ylds` (WT x WO 16-bit, this wave's own, same chunk-XOR-token layout
 // as loss_rows_lds), then the wave writes whole 128-byte lines, 8 lines per instruction.
-// Storing straight from the accumulator layout writes 8-byte pieces of 32 lines per instruction.
-template <typename YT, int FA, int FB>
-__device__ __forceinline__ void store_rows_lds(const GemmDev& a, f32x16 (&acc)[FA][FB], const float* tsc,
+// Storing straight from the accumulator layout writes 8-byte pieces of 16 or 32 lines per instruction.
+template <typename YT, typename L, typename Acc>
+__device__ __forceinline__ void store_rows_lds(const GemmDev& a, const Acc& acc, const float* tsc,
                                                int64_t ow, int64_t tw, unsigned char* ylds) {
-  constexpr int WO = FA * 32, WT = FB * 32;
+  constexpr int WO = L::WO, WT = L::WT;
   constexpr int CPR = WO / 8, RPI = 64 / CPR;
   static_assert(CPR == 16 && WT % RPI == 0, "copy shape");
-  const int lane = threadIdx.x & 63, frow = lane & 31, fhi = lane >> 5;
+  const int lane = threadIdx.x & 63;
 #pragma unroll
-  for (int j = 0; j < FB; ++j) {
-    const int tok = j * 32 + frow;
+  for (int tb = 0; tb < L::NTB; ++tb) {
+    const int tok = L::tok(tb, lane);
     const float sg = tsc ? tsc[tw + tok] : 1.0f;
 #pragma unroll
-    for (int i = 0; i < FA; ++i)
-#pragma unroll
-      for (int q = 0; q < 4; ++q) {
-        uint2 u;
-        u.x = (uint32_t)YT::from_float(sg * acc[i][j][q * 4]) | ((uint32_t)YT::from_float(sg * acc[i][j][q * 4 + 1]) << 16);
-        u.y = (uint32_t)YT::from_float(sg * acc[i][j][q * 4 + 2]) | ((uint32_t)YT::from_float(sg * acc[i][j][q * 4 + 3]) << 16);
-        *reinterpret_cast<uint2*>(ylds + tok * (WO * 2) + (((i * 4 + q) ^ (tok & 15)) << 4) + fhi * 8) = u;
-      }
+    for (int q = 0; q < L::NQ; ++q) {
+      const int o = L::row(q, lane);
+      uint2 u;
+      u.x = (uint32_t)YT::from_float(sg * L::get(acc, q, tb, 0)) | ((uint32_t)YT::from_float(sg * L::get(acc, q, tb, 1)) << 16);
+      u.y = (uint32_t)YT::from_float(sg * L::get(acc, q, tb, 2)) | ((uint32_t)YT::from_float(sg * L::get(acc, q, tb, 3)) << 16);
+      *reinterpret_cast<uint2*>(ylds + tok * (WO * 2) + (((o >> 3) ^ (tok & 15)) << 4) + ((o >> 2) & 1) * 8) = u;
+    }
   }
   uint16_t* Y = (uint16_t*)a.Yout;
   const int cr = lane / CPR, cc = lane % CPR;
@@ -247,67 +291,70 @@ __device__ __forceinline__ void store_rows_lds(const GemmDev& a, f32x16 (&acc)[F
 }
 
 // ---------------------------------------------------------------------------
-// Tile epilogue shared by both kernels.  Accumulator layout of a 32x32
-// fragment: lane holds column (lane%32) and rows 8*(v/4) + 4*(lane/32) + v%4,
-// v = 0..15.  The block's waves form an NWO x NWT grid; wave (wo, wt) owns
-// output rows [wo*WO, +WO) and tokens [wt*WT, +WT) of the tile at (o0, t0).
-// `red` holds one float per wave, `rows` NWO x BT floats (per-token row sums;
-// only used by EPI_LOSS_TOK).  Every wave of the block must call this.
-template <int EPI, int FA, int FB, int NWO, int NWT, int BT, bool YLDS = false>
-__device__ __forceinline__ void tile_epilogue(const GemmDev& a, f32x16 (&acc)[FA][FB], int cand, int to,
+// Tile epilogue shared by both kernels; L is the accumulator layout (Acc32 / Acc16).  The block's
+// waves form an NWO x NWT grid; wave (wo, wt) owns output rows [wo*WO, +WO) and tokens
+// [wt*WT, +WT) of the tile at (o0, t0).  `red` holds one float per wave, `rows` NWO x BT floats
+// (per-token row sums; only used by EPI_LOSS_TOK).  Every wave of the block must call this.
+template <int EPI, typename L, int NWO, int NWT, int BT, bool YLDS, typename Acc>
+__device__ __forceinline__ void tile_epilogue(const GemmDev& a, const Acc& acc, int cand, int to,
                                               int tt, int64_t o0, int64_t t0, int wo, int wt,
                                               float* red, float* rows) {
-  constexpr int WO = FA * 32, WT = FB * 32, NW = NWO * NWT, NT = NW * 64;
+  constexpr int WO = L::WO, WT = L::WT, NW = NWO * NWT, NT = NW * 64;
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-  const int frow = lane & 31, fhi = lane >> 5;
   const float* tsc = a.tok_scale ? a.tok_scale + (int64_t)cand * a.n_tok : nullptr;
   if (EPI == EPI_STORE) {
-    if (YLDS && a.odt != TLQ_F32 && (o0 + NWO * WO <= a.c_out) && (t0 + BT <= a.n_tok) && (a.ldo % 8) == 0 &&
-        ((uintptr_t)a.Yout % 16) == 0) {
-      unsigned char* ylds = reinterpret_cast<unsigned char*>(rows) + wave * (WO * WT * 2);
-      if (a.odt == TLQ_F16) store_rows_lds<F16, FA, FB>(a, acc, tsc, o0 + wo * WO, t0 + wt * WT, ylds);
-      else store_rows_lds<BF16, FA, FB>(a, acc, tsc, o0 + wo * WO, t0 + wt * WT, ylds);
-      return;
+    if constexpr (YLDS) {
+      if (a.odt != TLQ_F32 && (o0 + NWO * WO <= a.c_out) && (t0 + BT <= a.n_tok) && (a.ldo % 8) == 0 &&
+          ((uintptr_t)a.Yout % 16) == 0) {
+        unsigned char* ylds = reinterpret_cast<unsigned char*>(rows) + wave * (WO * WT * 2);
+        if (a.odt == TLQ_F16) store_rows_lds<F16, L>(a, acc, tsc, o0 + wo * WO, t0 + wt * WT, ylds);
+        else store_rows_lds<BF16, L>(a, acc, tsc, o0 + wo * WO, t0 + wt * WT, ylds);
+        return;
+      }
     }
 #pragma unroll
-    for (int j = 0; j < FB; ++j) {
-      const int64_t t = t0 + wt * WT + j * 32 + frow;
+    for (int tb = 0; tb < L::NTB; ++tb) {
+      const int64_t t = t0 + wt * WT + L::tok(tb, lane);
       if (t >= a.n_tok) continue;
       const float sg = tsc ? tsc[t] : 1.0f;
 #pragma unroll
-      for (int i = 0; i < FA; ++i)
-#pragma unroll
-        for (int q = 0; q < 4; ++q) {
-          const int64_t o = o0 + wo * WO + i * 32 + q * 8 + fhi * 4;
-          float y[4] = {sg * acc[i][j][q * 4], sg * acc[i][j][q * 4 + 1], sg * acc[i][j][q * 4 + 2],
-                        sg * acc[i][j][q * 4 + 3]};
-          if (o + 3 < a.c_out) store_y4(a.Yout, a.odt, t * a.ldo + o, y);
-          else
-            for (int r = 0; r < 4; ++r)
-              if (o + r < a.c_out) store_y1(a.Yout, a.odt, t * a.ldo + o + r, y[r]);
-        }
+      for (int q = 0; q < L::NQ; ++q) {
+        const int64_t o = o0 + wo * WO + L::row(q, lane);
+        float y[4] = {sg * L::get(acc, q, tb, 0), sg * L::get(acc, q, tb, 1), sg * L::get(acc, q, tb, 2),
+                      sg * L::get(acc, q, tb, 3)};
+        if (o + 3 < a.c_out) store_y4(a.Yout, a.odt, t * a.ldo + o, y);
+        else
+          for (int r = 0; r < 4; ++r)
+            if (o + r < a.c_out) store_y1(a.Yout, a.odt, t * a.ldo + o + r, y[r]);
+      }
     }
     return;
   }
   // Interior tiles (the common case) take a branch-free body specialised on the Y_ref
   // type; edge tiles and odd strides take the guarded one.
   float part = 0.0f;
-  float sq[FB];
+  float sq[L::NTB];
   const bool interior = (o0 + NWO * WO <= a.c_out) && (t0 + BT <= a.n_tok);
-  if (YLDS && EPI == EPI_LOSS && interior && a.ydt != TLQ_F32) {
-    unsigned char* ylds = reinterpret_cast<unsigned char*>(rows) + wave * (WO * WT * 2);
-    if (a.ydt == TLQ_F16) loss_rows_lds<F16, FA, FB>(a, acc, tsc, o0 + wo * WO, t0 + wt * WT, sq, part, ylds);
-    else loss_rows_lds<BF16, FA, FB>(a, acc, tsc, o0 + wo * WO, t0 + wt * WT, sq, part, ylds);
-  } else
-  if (interior && a.ydt == TLQ_F16) loss_rows<TLQ_F16, true, FA, FB>(a, acc, tsc, o0 + wo * WO, t0 + wt * WT, sq, part);
-  else if (interior && a.ydt == TLQ_F32) loss_rows<TLQ_F32, true, FA, FB>(a, acc, tsc, o0 + wo * WO, t0 + wt * WT, sq, part);
-  else if (interior) loss_rows<TLQ_BF16, true, FA, FB>(a, acc, tsc, o0 + wo * WO, t0 + wt * WT, sq, part);
-  else loss_rows<-1, false, FA, FB>(a, acc, tsc, o0 + wo * WO, t0 + wt * WT, sq, part);
+  const int64_t ow = o0 + wo * WO, tw = t0 + wt * WT;
+  bool done = false;
+  if constexpr (YLDS && EPI == EPI_LOSS) {
+    if (interior && a.ydt != TLQ_F32 && (a.ldy % 8) == 0 && ((uintptr_t)a.Yref % 16) == 0) {
+      unsigned char* ylds = reinterpret_cast<unsigned char*>(rows) + wave * (WO * WT * 2);
+      if (a.ydt == TLQ_F16) loss_rows_lds<F16, L>(a, acc, tsc, ow, tw, sq, part, ylds);
+      else loss_rows_lds<BF16, L>(a, acc, tsc, ow, tw, sq, part, ylds);
+      done = true;
+    }
+  }
+  if (done) {}
+  else if (interior && a.ydt == TLQ_F16) loss_rows<TLQ_F16, true, L>(a, acc, tsc, ow, tw, sq, part);
+  else if (interior && a.ydt == TLQ_F32) loss_rows<TLQ_F32, true, L>(a, acc, tsc, ow, tw, sq, part);
+  else if (interior) loss_rows<TLQ_BF16, true, L>(a, acc, tsc, ow, tw, sq, part);
+  else loss_rows<-1, false, L>(a, acc, tsc, ow, tw, sq, part);
   if (EPI == EPI_LOSS_TOK) {
 #pragma unroll
-    for (int j = 0; j < FB; ++j) {
-      const float both = sq[j] + __shfl_xor(sq[j], 32, 64);
-      if (fhi == 0) rows[wo * BT + wt * WT + j * 32 + frow] = both;
+    for (int tb = 0; tb < L::NTB; ++tb) {
+      const float both = L::tok_sum(sq[tb]);
+      if (L::row(0, lane) == 0) rows[wo * BT + wt * WT + L::tok(tb, lane)] = both;
     }
   }
 #pragma unroll
@@ -473,8 +520,8 @@ __global__ __launch_bounds__((BO / WO) * (BT / WT) * 64) void gemm_kernel(GemmDe
   }
 
   // the tile memory is free now: row sums of the per-token variant reuse it
-  tile_epilogue<EPI, FA, FB, NWO, NWT, BT>(a, acc, cand, to, tt, o0, t0, wo, wt, red,
-                                           reinterpret_cast<float*>(lds));
+  tile_epilogue<EPI, Acc32<FA, FB>, NWO, NWT, BT, false>(a, acc, cand, to, tt, o0, t0, wo, wt, red,
+                                                         reinterpret_cast<float*>(lds));
 }
 
 // ---------------------------------------------------------------------------
@@ -506,12 +553,8 @@ __device__ __forceinline__ void lds_read128(u32x4& v, uint32_t addr) {
 }
 // Wait for every outstanding LDS read; the fragments are tied through the
 // statement so that nothing consuming them can be scheduled above it.
-__device__ __forceinline__ void lds_wait6(u32x4& f0, u32x4& f1, u32x4& f2, u32x4& f3, u32x4& f4,
-                                          u32x4& f5) {
-  asm volatile("s_waitcnt lgkmcnt(0)"
-               : "+v"(f0), "+v"(f1), "+v"(f2), "+v"(f3), "+v"(f4), "+v"(f5)
-               :
-               : "memory");
+__device__ __forceinline__ void lds_wait4(u32x4& f0, u32x4& f1, u32x4& f2, u32x4& f3) {
+  asm volatile("s_waitcnt lgkmcnt(0)" : "+v"(f0), "+v"(f1), "+v"(f2), "+v"(f3) : : "memory");
 }
 __device__ __forceinline__ void lds_wait8(u32x4& f0, u32x4& f1, u32x4& f2, u32x4& f3, u32x4& f4,
                                           u32x4& f5, u32x4& f6, u32x4& f7) {
@@ -519,11 +562,6 @@ __device__ __forceinline__ void lds_wait8(u32x4& f0, u32x4& f1, u32x4& f2, u32x4
                : "+v"(f0), "+v"(f1), "+v"(f2), "+v"(f3), "+v"(f4), "+v"(f5), "+v"(f6), "+v"(f7)
                :
                : "memory");
-}
-// F[I] <- 16 bytes at addr + I * STEP for I = 0..N-1 (offsets must be immediates)
-template <int STEP, int... I>
-__device__ __forceinline__ void lds_read_seq(u32x4* F, uint32_t addr, std::integer_sequence<int, I...>) {
-  (lds_read128<I * STEP>(F[I], addr), ...);
 }
 template <int I, int N, typename Fn>
 __device__ __forceinline__ void static_for(Fn&& f) {
@@ -537,20 +575,34 @@ __device__ __forceinline__ void wait_vmcnt() {
   asm volatile("s_waitcnt vmcnt(%0)" ::"n"(N) : "memory");
 }
 
-template <typename T, int BK_, int NSTAGE, int NWO, int NWT, int EPI>
-__global__ __launch_bounds__(NWO * NWT * 64) void gemm_dma_kernel(GemmDev a) {
+// Block tile 256 (o) x 256 (t), k-tile 64, 8 waves in a 2 x 4 grid; a wave owns 128 x 64 outputs
+// = 8 x 4 accumulator tiles of the 16x16x32 MFMA (128 registers).  A k-tile is two k32 steps; a
+// step is split into two PHASES of 16 MFMAs (output rows 0-63, then 64-127 of the wave tile), so
+// only four weight fragments and four token fragments are live per phase and both sets can be
+// double-buffered in 64 registers:
+//   phase 0: rows  0-63  x step 0   reads meanwhile: weight fragments of rows 64-127, step 0
+//   phase 1: rows 64-127 x step 0   reads meanwhile: weight fragments of rows 0-63 and the token
+//                                   fragments of step 1
+//   phase 2: rows  0-63  x step 1   reads meanwhile: weight fragments of rows 64-127, step 1
+//   -- every fragment of the k-tile is in registers: wait for this wave's loads of the next
+//      k-tile, block barrier --
+//   phase 3: rows 64-127 x step 1   reads meanwhile: first fragments of the NEXT k-tile; the 8
+//                                   LDS-DMA loads that refill the slot just freed
+// One side operation is slotted behind each MFMA, so that neither the LDS queue nor the
+// texture-address queue sees a burst that would hold back the in-order MFMA issue.
+template <typename T, int NSTAGE, int EPI>
+__global__ __launch_bounds__(512) void gemm_dma_kernel(GemmDev a) {
 #if defined(__HIP_DEVICE_COMPILE__)  // the body uses gfx950 builtins the host pass cannot parse
-  constexpr int BO = 256, BT = 256, WO = BO / NWO, WT = BT / NWT, NW = NWO * NWT;
-  constexpr int FA = WO / 32, FB = WT / 32, NF = FA + FB, KK = BK_ / 16;
-  static_assert(NF == 6 || NF == 8, "fragment count");
-  static_assert(BK_ == 64, "the chunk swizzle below is written for 128-byte LDS rows");
+  constexpr int BK_ = 64, BO = 256, BT = 256, NWO = 2, NWT = 4, NW = NWO * NWT, WO = BO / NWO, WT = BT / NWT;
+  constexpr int IA = WO / 16, JB = WT / 16;   // accumulator tiles per wave: 8 x 4
+  static_assert(IA == 8 && JB == 4, "phase structure below is written for 128 x 64 wave tiles");
   constexpr int RB = BK_ * 2;             // bytes per LDS row
   constexpr int CPR = BK_ / 8;            // 16-byte chunks per row
   constexpr int STAGE = (BO + BT) * RB;
   constexpr int RPD = 64 / CPR;           // rows covered by one wave-wide load
   constexpr int DPO = BO / RPD / NW;      // loads per wave per operand per k-tile
   constexpr int LPS = 2 * DPO;            // loads per wave per k-tile
-  static_assert(KK % 2 == 0 && NSTAGE >= 2 && (NSTAGE - 1) * LPS < 64, "pipeline shape");
+  static_assert(NSTAGE == 2 && LPS == 8, "pipeline shape");
   __shared__ __attribute__((aligned(1024))) unsigned char lds[NSTAGE * STAGE];
   __shared__ float red[NW];
 
@@ -572,7 +624,8 @@ __global__ __launch_bounds__(NWO * NWT * 64) void gemm_dma_kernel(GemmDev a) {
   const __amdgpu_buffer_rsrc_t rB = __builtin_amdgcn_make_buffer_rsrc(
       (void*)pB, 0, (int)(((vrt - 1) * a.ldx + a.c_in) * 2), 0x00020000);
 
-  // per-lane global byte offsets of the chunks this lane fetches
+  // per-lane global byte offsets of the chunks this lane fetches: LDS slot `p` of row r holds
+  // chunk p ^ ((r / 2) % 8)
   int voa[DPO], vob[DPO];
 #pragma unroll
   for (int j = 0; j < DPO; ++j) {
@@ -589,127 +642,107 @@ __global__ __launch_bounds__(NWO * NWT * 64) void gemm_dma_kernel(GemmDev a) {
   // delivers zeros.
   const int64_t nk = a.c_in / BK_;
   constexpr int kOutOfRange = (int)0x80000000u;
+  auto dma1 = [&](auto dc, unsigned char* sbase, bool live, int so) {
+    constexpr int d = decltype(dc)::value, j = d / 2;
+    if constexpr ((d & 1) == 0)
+      __builtin_amdgcn_raw_ptr_buffer_load_lds(rA, (lds_ptr_t)(sbase + (j * NW + wave) * 1024), 16,
+                                               live ? voa[j] : kOutOfRange, so, 0, 0);
+    else
+      __builtin_amdgcn_raw_ptr_buffer_load_lds(rB, (lds_ptr_t)(sbase + BO * RB + (j * NW + wave) * 1024), 16,
+                                               live ? vob[j] : kOutOfRange, so, 0, 0);
+  };
   auto issue = [&](int64_t kt) {
-    const int st = (int)(kt % NSTAGE);
     const bool live = kt < nk;
     const int so = live ? (int)(kt * BK_ * 2) : 0;
-    unsigned char* sb = lds + st * STAGE;
-#pragma unroll
-    for (int j = 0; j < DPO; ++j) {
-      __builtin_amdgcn_raw_ptr_buffer_load_lds(rA, (lds_ptr_t)(sb + (j * NW + wave) * 1024), 16,
-                                               live ? voa[j] : kOutOfRange, so, 0, 0);
-      __builtin_amdgcn_raw_ptr_buffer_load_lds(rB, (lds_ptr_t)(sb + BO * RB + (j * NW + wave) * 1024),
-                                               16, live ? vob[j] : kOutOfRange, so, 0, 0);
-    }
+    unsigned char* sb = lds + (int)(kt % NSTAGE) * STAGE;
+    static_for<0, LPS>([&](auto dc) { dma1(dc, sb, live, so); });
   };
 
-  // fragment read addresses (bytes from the start of a stage)
-  const int frow = lane & 31, fhi = lane >> 5;
+  // fragment read addresses (bytes from the start of a stage): lane -> row lane % 16 of a 16-row
+  // block and 16-byte chunk lane / 16 of the k32 step (the MFMA takes k = 8 * (lane / 16) + [0, 8)
+  // from both operands, so any chunk order is right as long as both use the same one)
+  const int frow = lane & 15, fq = lane >> 4;
   const uint32_t lds0 = (uint32_t)(uintptr_t)(lds_ptr_t)lds;
-  uint32_t offA[KK], offB[KK];
+  uint32_t offA[2], offB[2];
 #pragma unroll
-  for (int kk = 0; kk < KK; ++kk) {
-    const int c = kk * 2 + fhi;
+  for (int st = 0; st < 2; ++st) {
+    const int c = st * 4 + fq;
     const int p = c ^ ((frow >> 1) & 7);
     const uint32_t o = (uint32_t)(frow * RB + p * 16);
-    offA[kk] = lds0 + o + (wo * WO) * RB;
-    offB[kk] = lds0 + o + BO * RB + (wt * WT) * RB;
+    offA[st] = lds0 + o + (wo * WO) * RB;
+    offB[st] = lds0 + o + BO * RB + (wt * WT) * RB;
   }
-  u32x4 F[2][NF];
-  f32x16 acc[FA][FB];
+  u32x4 Fa[2][4], Fb[2][4];   // weight fragments (double-buffered per phase), token fragments (per k32 step)
+  f32x4 acc[IA][JB];
 #pragma unroll
-  for (int i = 0; i < FA; ++i)
+  for (int i = 0; i < IA; ++i)
 #pragma unroll
-    for (int j = 0; j < FB; ++j)
+    for (int j = 0; j < JB; ++j)
 #pragma unroll
-      for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.0f;
+      for (int v = 0; v < 4; ++v) acc[i][j][v] = 0.0f;
 
-  // Single operations, indexed at compile time so that every LDS offset is an
-  // immediate and every fragment stays in a fixed register.
-  auto read1 = [&](auto bufc, uint32_t sa, uint32_t sb2, auto rc) {
-    constexpr int buf = decltype(bufc)::value, r = decltype(rc)::value;
-    if constexpr (r < FA) lds_read128<r * 32 * RB>(F[buf][r], sa);
-    else lds_read128<(r - FA) * 32 * RB>(F[buf][r], sb2);
-  };
-  auto mma1 = [&](auto bufc, auto mc) {
-    constexpr int buf = decltype(bufc)::value, m = decltype(mc)::value, i = m / FB, j = m % FB;
-    acc[i][j] = Mma<T>::run(__builtin_bit_cast(uint4, F[buf][i]),
-                            __builtin_bit_cast(uint4, F[buf][FA + j]), acc[i][j]);
-  };
-  auto fwait = [&](auto bufc) {
-    constexpr int buf = decltype(bufc)::value;
-    if constexpr (NF == 6)
-      lds_wait6(F[buf][0], F[buf][1], F[buf][2], F[buf][3], F[buf][4], F[buf][5]);
-    else
-      lds_wait8(F[buf][0], F[buf][1], F[buf][2], F[buf][3], F[buf][4], F[buf][5], F[buf][6], F[buf][7]);
-  };
-  // One phase = the FA*FB MFMAs of one k16 step on fragment buffer CB, with the
-  // "side" operations of the phase (NR fragment reads into the other buffer,
-  // then ND LDS-DMA loads of k-tile `dkt`) slotted two at a time behind the
-  // leading MFMAs, so that neither the LDS queue nor the texture-address queue
-  // sees a burst that would hold back the in-order MFMA issue.
-  constexpr int M = FA * FB;
-  auto phase = [&](auto cbc, auto nrc, auto ndc, uint32_t sa, uint32_t sb2, int64_t dkt) {
-    constexpr int CB = decltype(cbc)::value, NR = decltype(nrc)::value, ND = decltype(ndc)::value;
-    static_assert(NR + ND <= 2 * M, "too many side operations for one phase");
-    const int dst = (int)(dkt % NSTAGE);
+  // One phase: the 16 MFMAs of weight buffer AB x token buffer BB into output rows HALF, with one
+  // side operation behind each: first the weight fragments of half RH into buffer AB ^ 1 (from
+  // `ra`), then - if RDB - the token fragments into buffer BB ^ 1 (from `rb`), then ND LDS-DMA loads
+  // of k-tile `dkt`.
+  auto phase = [&](auto abc, auto bbc, auto halfc, auto rhc, auto rdbc, auto ndc, uint32_t ra, uint32_t rb,
+                   int64_t dkt) {
+    constexpr int AB = decltype(abc)::value, BB = decltype(bbc)::value, HALF = decltype(halfc)::value;
+    constexpr int RH = decltype(rhc)::value, ND = decltype(ndc)::value;
+    constexpr bool RDB = decltype(rdbc)::value != 0;
+    constexpr int NR = 4 + (RDB ? 4 : 0);
+    static_assert(NR + ND <= 16, "one side operation per MFMA");
     const bool live = dkt < nk;
     const int so = live ? (int)(dkt * BK_ * 2) : 0;
-    unsigned char* sbase = lds + dst * STAGE;
-    static_for<0, M>([&](auto mc) {
-      constexpr int m = decltype(mc)::value;
-      mma1(cbc, mc);
-      static_for<2 * m, (2 * m + 2 < NR + ND ? 2 * m + 2 : NR + ND)>([&](auto sc) {
-        constexpr int sidx = decltype(sc)::value;
-        if constexpr (sidx < NR) {
-          read1(std::integral_constant<int, CB ^ 1>{}, sa, sb2, sc);
-        } else {
-          constexpr int d = sidx - NR, j = d / 2;
-          if constexpr ((d & 1) == 0)
-            __builtin_amdgcn_raw_ptr_buffer_load_lds(rA, (lds_ptr_t)(sbase + (j * NW + wave) * 1024), 16,
-                                                     live ? voa[j] : kOutOfRange, so, 0, 0);
-          else
-            __builtin_amdgcn_raw_ptr_buffer_load_lds(
-                rB, (lds_ptr_t)(sbase + BO * RB + (j * NW + wave) * 1024), 16,
-                live ? vob[j] : kOutOfRange, so, 0, 0);
-        }
-      });
+    unsigned char* sbase = lds + (int)(dkt % NSTAGE) * STAGE;
+    static_for<0, 16>([&](auto mc) {
+      constexpr int m = decltype(mc)::value, ib = m / 4, jb = m % 4;
+      acc[HALF * 4 + ib][jb] = Mma16<T>::run(__builtin_bit_cast(uint4, Fa[AB][ib]),
+                                             __builtin_bit_cast(uint4, Fb[BB][jb]), acc[HALF * 4 + ib][jb]);
+      if constexpr (m < 4) lds_read128<(RH * 4 + m) * 16 * RB>(Fa[AB ^ 1][m], ra);
+      else if constexpr (m < NR) lds_read128<(m - 4) * 16 * RB>(Fb[BB ^ 1][m - 4], rb);
+      else if constexpr (m < NR + ND) dma1(std::integral_constant<int, m - NR>{}, sbase, live, so);
       __builtin_amdgcn_sched_barrier(0);
     });
   };
-  using C0 = std::integral_constant<int, 0>;
+  using I0 = std::integral_constant<int, 0>;
+  using I1 = std::integral_constant<int, 1>;
+  using I8 = std::integral_constant<int, LPS>;
 
   // prologue: fill the whole ring, wait for k-tile 0, fetch its first fragments
 #pragma unroll
   for (int s = 0; s < NSTAGE; ++s) issue(s);
   wait_vmcnt<(NSTAGE - 1) * LPS>();
   __builtin_amdgcn_s_barrier();
-  static_for<0, NF>([&](auto rc) { read1(C0{}, offA[0], offB[0], rc); });
-  fwait(C0{});
+  static_for<0, 4>([&](auto mc) {
+    constexpr int m = decltype(mc)::value;
+    lds_read128<m * 16 * RB>(Fa[0][m], offA[0]);
+    lds_read128<m * 16 * RB>(Fb[0][m], offB[0]);
+  });
+  lds_wait8(Fa[0][0], Fa[0][1], Fa[0][2], Fa[0][3], Fb[0][0], Fb[0][1], Fb[0][2], Fb[0][3]);
   for (int64_t kt = 0; kt < nk; ++kt) {
     const uint32_t so_cur = (uint32_t)((kt % NSTAGE) * STAGE);
-    static_for<0, KK - 1>([&](auto kc) {
-      constexpr int kk = decltype(kc)::value;
-      phase(std::integral_constant<int, kk & 1>{}, std::integral_constant<int, NF>{}, C0{},
-            offA[kk + 1] + so_cur, offB[kk + 1] + so_cur, 0);
-      fwait(std::integral_constant<int, (kk + 1) & 1>{});
-    });
+    phase(I0{}, I0{}, I0{}, I1{}, I0{}, I0{}, offA[0] + so_cur, 0u, 0);
+    lds_wait4(Fa[1][0], Fa[1][1], Fa[1][2], Fa[1][3]);
+    phase(I1{}, I0{}, I1{}, I0{}, I1{}, I0{}, offA[1] + so_cur, offB[1] + so_cur, 0);
+    lds_wait8(Fa[0][0], Fa[0][1], Fa[0][2], Fa[0][3], Fb[1][0], Fb[1][1], Fb[1][2], Fb[1][3]);
+    phase(I0{}, I1{}, I0{}, I1{}, I0{}, I0{}, offA[1] + so_cur, 0u, 0);
+    lds_wait4(Fa[1][0], Fa[1][1], Fa[1][2], Fa[1][3]);
     // every fragment of k-tile kt is in registers: its slot can be refilled once all
     // waves are here, and k-tile kt+1 has landed once this wave's share of it has
     wait_vmcnt<(NSTAGE - 2) * LPS>();
     __builtin_amdgcn_s_barrier();
     __builtin_amdgcn_sched_barrier(0);
     const uint32_t so_next = (uint32_t)(((kt + 1) % NSTAGE) * STAGE);
-    phase(std::integral_constant<int, (KK - 1) & 1>{}, std::integral_constant<int, NF>{},
-          std::integral_constant<int, LPS>{}, offA[0] + so_next, offB[0] + so_next, kt + NSTAGE);
-    fwait(C0{});
+    phase(I1{}, I1{}, I1{}, I0{}, I1{}, I8{}, offA[0] + so_next, offB[0] + so_next, kt + NSTAGE);
+    lds_wait8(Fa[0][0], Fa[0][1], Fa[0][2], Fa[0][3], Fb[0][0], Fb[0][1], Fb[0][2], Fb[0][3]);
   }
   wait_vmcnt<0>();
   __syncthreads();
 
   // every LDS-DMA write has landed and every wave is past its last fragment read:
-  // the tile memory is free for the per-token row sums
-  tile_epilogue<EPI, FA, FB, NWO, NWT, BT, (NSTAGE * STAGE >= NW * WO * WT * 2) && FA == 4>(
+  // the tile memory is free for the per-token row sums and the Y_ref / output staging
+  tile_epilogue<EPI, Acc16<IA, JB>, NWO, NWT, BT, (NSTAGE * STAGE >= NW * WO * WT * 2)>(
       a, acc, cand, to, tt, o0, t0, wo, wt, red, reinterpret_cast<float*>(lds));
 #endif
 }
@@ -718,7 +751,7 @@ __global__ __launch_bounds__(NWO * NWT * 64) void gemm_dma_kernel(GemmDev a) {
 constexpr int kBO = 256, kBT = 256, kWO = 128, kWT = 64;
 constexpr int64_t kChunkBytes = (int64_t)128 << 20;
 constexpr int kDmaBK = 64, kDmaStages = 2;   // k-tile depth and LDS ring slots of the pipelined kernel
-constexpr int kDmaNWO = 2, kDmaNWT = 4;      // its 2 x 4 wave grid (128 x 64 outputs per wave)
+constexpr int kDmaThreads = 512;             // its 2 x 4 wave grid (128 x 64 outputs per wave)
 
 void gemm_tile_counts(int64_t n_tok, int64_t c_out, int64_t* tiles_o, int64_t* tiles_t) {
   *tiles_o = ceil_div(c_out, kBO);
@@ -776,11 +809,10 @@ static hipError_t launch_gemm(const GemmArgs& g, const char* name, hipStream_t s
   // the pipelined kernel needs whole k-tiles and 32-bit byte offsets inside a 256-row panel
   const bool dma = (g.c_in % kDmaBK) == 0 && g.ldw < (1 << 21) && g.ldx < (1 << 21);
   if (dma) {
-    constexpr int NTD = kDmaNWO * kDmaNWT * 64;
     if (!g.bf16)
-      gemm_dma_kernel<F16, kDmaBK, kDmaStages, kDmaNWO, kDmaNWT, EPI><<<(unsigned)blocks, NTD, 0, stream>>>(d);
+      gemm_dma_kernel<F16, kDmaStages, EPI><<<(unsigned)blocks, kDmaThreads, 0, stream>>>(d);
     else
-      gemm_dma_kernel<BF16, kDmaBK, kDmaStages, kDmaNWO, kDmaNWT, EPI><<<(unsigned)blocks, NTD, 0, stream>>>(d);
+      gemm_dma_kernel<BF16, kDmaStages, EPI><<<(unsigned)blocks, kDmaThreads, 0, stream>>>(d);
   } else {
     if (!g.bf16) gemm_kernel<F16, kBO, kBT, kWO, kWT, EPI><<<(unsigned)blocks, NT, 0, stream>>>(d);
     else gemm_kernel<BF16, kBO, kBT, kWO, kWT, EPI><<<(unsigned)blocks, NT, 0, stream>>>(d);
