@@ -2,24 +2,26 @@
 // epilogue (Sec. 3.2.1 objective; Sec. 2.2 smoothing identity), and the same
 // contraction with a store epilogue (f_fp of Sec. 3.2.1; PassAct2 output).
 //
-// The kernel computes  D[o, t] = sum_c What[o, c] * X[t, c]  on 32x32x16
-// fp16/bf16 MFMA with float accumulation.  `What` stacks the folded operands
+// The kernels compute  D[o, t] = sum_c What[o, c] * X[t, c]  on fp16/bf16 MFMA
+// with float accumulation.  `What` stacks the folded operands
 // of all candidates ([n_cand * c_out, c_in]), so the alpha grid is simply an
 // extra stretch of the o dimension and every X tile is shared by all
 // candidates.  In the loss epilogue each lane owns one token column of its
-// 32x32 fragments: it subtracts the accumulators from Y_ref, squares, sums
+// accumulator tiles: it subtracts the accumulators from Y_ref, squares, sums
 // over its output rows, multiplies by that token's weight and the block
 // reduces to ONE float per (candidate, tile).  Candidate outputs never reach
 // HBM.
 //
-// Tiling (wave64): block tile BO x BT outputs, BK = 64; waves own WO x WT
+// Two kernels share the tile epilogues and the block -> tile map:
+//   gemm_dma_kernel  the pipelined one (c_in % 64 == 0): 16x16x32 MFMA, operands brought
+//                    into LDS by LDS-DMA loads, two 64 KB stages, hand-placed waits;
+//   gemm_kernel      the general one: 32x32x16 MFMA, register-staged loads.
+// Tiling (wave64): block tile 256 x 256 outputs, k-tile 64; waves own 128 x 64
 // sub-tiles.  Both operands are K-contiguous in memory, so a fragment is one
 // 16-byte LDS read per lane.  LDS rows are 128 B (64 halves) and the eight
 // 16-byte chunks of a row are XOR-swizzled with (row/2)%8 so that the 16 lanes
 // served together by a 128-bit LDS access touch 16 different bank groups, for
 // the fragment reads and for the tile writes alike.
-// Two LDS stages: the global loads of k-tile i+1 are issued before the MFMAs of
-// k-tile i and written to the other stage afterwards; one barrier per k-tile.
 #include <cstdlib>
 #include <utility>
 
@@ -419,6 +421,8 @@ __host__ __device__ __forceinline__ bool decode_tile(const GemmDev& a, int64_t b
   return to < a.tiles_o && tt < a.tiles_t;
 }
 
+// General kernel: two LDS stages; the global loads of k-tile i+1 are issued before the MFMAs of
+// k-tile i and written to the other stage afterwards; one barrier per k-tile.
 template <typename T, int BO, int BT, int WO, int WT, int EPI>
 __global__ __launch_bounds__((BO / WO) * (BT / WT) * 64) void gemm_kernel(GemmDev a) {
   constexpr int NWO = BO / WO, NWT = BT / WT, NW = NWO * NWT, NT = NW * 64;
