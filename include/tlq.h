@@ -239,6 +239,41 @@ tlq_status tlq_apply_best_prepared(const void* X, int64_t n_tok, int64_t c_in, i
                                    void* workspace, size_t workspace_bytes, void* stream,
                                    const void* prepared);
 
+/* ---- the weight-only search in second-moment form (Sec. 3.2.1 objective with f_q linear in x,
+ * i.e. act_bits == 0).  For f_fp(x) = x W^T and f_q(x) = x What_k^T the objective
+ *   sum_t token_w[t] (1/c_out) ||f_fp(x_t) - f_q(x_t)||^2  =  (1/c_out) sum_o d_o^T G d_o,
+ *   d_o = row o of W - What_k,   G = sum_t token_w[t] x_t x_t^T   [c_in, c_in],
+ * so the tokens enter through G alone.  G does not depend on the candidate or on the linear:
+ * linears that share an input (q/k/v, gate/up) share one G, and a candidate then costs
+ * 2 c_out c_in^2 flops instead of 2 n_tok c_in c_out.  It pays when n_tok is well above c_in.
+ * The target is the exact product x W^T (no rounded Y_ref enters), and no per-token error exists.
+ *
+ * tlq_token_gram writes a device-resident representation of G into `gram`
+ * (tlq_token_gram_bytes(c_in) bytes, 256-byte aligned, caller-owned): a double `factor` at byte 0,
+ * float col_scale[c_in] at byte 256, then (256-byte aligned) fp16 C[c_in, c_in], with
+ *   G[i,j] = factor * col_scale[i] * col_scale[j] * C[i,j];
+ * col_scale holds powers of two chosen so that |C| <= 2 whatever the spread of the channel
+ * magnitudes.  Tokens must lie inside the fp16 range (|x| < 65504) - beyond it the losses come out
+ * non-finite.  Workspace from the query.
+ * tlq_scale_search_gram is tlq_scale_search with (X, Y_ref, token_w) replaced by `gram`; x_stat
+ * [c_in] is required (tlq_x_stat of the same X).  act_bits != 0 -> TLQ_ERR_UNSUPPORTED.  Outputs,
+ * non-finite rule and tie rule as for tlq_scale_search. */
+size_t     tlq_token_gram_bytes(int64_t c_in);
+size_t     tlq_token_gram_workspace_bytes(int64_t n_tok, int64_t c_in);
+tlq_status tlq_token_gram(const void* X, int64_t n_tok, int64_t c_in, int64_t ldx,
+                          const float* token_w /*[n_tok]*/, const tlq_params* p,
+                          void* gram, size_t gram_bytes,
+                          void* workspace, size_t workspace_bytes, void* stream);
+size_t     tlq_scale_search_gram_workspace_bytes(int64_t c_in, int64_t c_out, int32_t n_alpha,
+                                                 const tlq_params* p);
+tlq_status tlq_scale_search_gram(const void* gram, int64_t c_in,
+                                 const void* W, int64_t c_out, int64_t ldw,
+                                 const float* alpha_grid, int32_t n_alpha, const tlq_params* p,
+                                 const float* x_stat /*[c_in]*/,
+                                 float* best_scales /*[c_in]*/, int32_t* best_idx /*[1]*/,
+                                 float* losses /*[n_alpha]*/, float* s_table_out /*[n_alpha,c_in] or NULL*/,
+                                 void* workspace, size_t workspace_bytes, void* stream);
+
 /* ---- full-precision layer output (Sec. 3.2.1 f_fp without bias):
  * Y[t,o] = sum_c X[t,c] W[o,c], float accumulation, stored as yref_dtype. */
 tlq_status tlq_ref_output(const void* X, int64_t n_tok, int64_t c_in, int64_t ldx,

@@ -47,7 +47,8 @@ Parity pins (see tests/test_oracle_pins.py): brute force on tiny layers
 (oracle/brute.py), hand-worked quantiser example (tests/golden), alpha=0 and
 alpha=1 closed forms, uniform-weight MSE, smoothing identity with an identity
 quantiser, grid idempotence, Delta^2/12 error energy (Sec. 2.2), power-of-two
-scale invariance, max-code closed form for the symmetric variant.
+scale invariance, max-code closed form for the symmetric variant, the
+quadratic-form identity of the token second-moment matrix.
 Every function of this module has at least one such pin; the sequential-chain
 module (oracle/chain.py) is pinned by tests/test_oracle_chain_pins.py and the
 decoder-stack module (oracle/stack.py) by tests/test_oracle_stack_pins.py.  Not pinned, and not
@@ -274,6 +275,18 @@ def weighted_layer_err(X, deq, Y_ref, token_w, s=None, inv_s=None):
     w-weighted sum over tokens).  Returns (L, e) in float64."""
     e = per_token_err(Y_ref, quantised_output(X, deq, s=s, inv_s=inv_s))
     return float((to_f64(token_w) * e).sum()), e
+
+
+def token_second_moment(X, token_w, rows=None, cols=None):
+    """G[i, j] = sum_t w_t x_t[i] x_t[j], float64 (all of it, or the listed rows x cols).
+
+    With Q_a = identity the quantised layer is linear in x, so the objective of Sec. 3.2.1 with
+    f_fp(x) = W x is  sum_t w_t (1/C_out) ||(W - What) x_t||^2 = (1/C_out) sum_o d_o^T G d_o  with
+    d_o the rows of W - What: this matrix is all the objective needs from the tokens."""
+    Xd, w = to_f64(X), to_f64(token_w)
+    A = Xd if rows is None else Xd[:, rows]
+    B = Xd if cols is None else Xd[:, cols]
+    return (A * w[:, None]).T @ B
 
 
 # --------------------------------------------------------------------------

@@ -21,7 +21,7 @@ OBJ = os.path.join(HERE, "_build")
 LIB = os.path.join(HERE, "libtlq.so")
 CEILING = os.path.join(HERE, "mfma_ceiling")
 
-SOURCES = ["api.hip", "stats.hip", "quant.hip", "gemm.hip", "glue.hip", "block.hip", "select.hip", "profile.hip", "noalloc.hip"]
+SOURCES = ["api.hip", "stats.hip", "quant.hip", "gemm.hip", "glue.hip", "block.hip", "select.hip", "profile.hip", "noalloc.hip", "gram.hip"]
 COMMON = ["--offload-arch=gfx950", "-O3", "-fPIC", "-std=c++17", "-I", os.path.join(ROOT, "include"),
           "-I", CSRC, "-Wall", "-Wno-unused-function",
           # keep hipcc from forming packed-fp32 instructions on its own

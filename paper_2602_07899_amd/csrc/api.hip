@@ -132,6 +132,43 @@ Prepared view_prepared(const void* buf) {
   return Prepared{(const uint32_t*)buf, (const uint16_t*)((const unsigned char*)buf + 256)};
 }
 
+// Second-moment form: the caller-held result of tlq_token_gram
+// [double factor : 256 bytes][float col_scale[c_in]][fp16 C[c_in, c_in]]
+struct GramView { double* factor; float* col_scale; uint16_t* C; size_t bytes; };
+GramView view_gram(void* buf, int64_t c_in) {
+  Carver c(buf);
+  GramView v;
+  v.factor = c.take<double>(1);
+  v.col_scale = c.take<float>((size_t)c_in);
+  v.C = c.take<uint16_t>((size_t)c_in * c_in);
+  v.bytes = c.off;
+  return v;
+}
+struct GramPlan { float* wmax; int* e; uint16_t* xst; float* H; int64_t kp; size_t bytes; };
+GramPlan plan_gram(void* ws, int64_t n_tok, int64_t c_in) {
+  GramPlan g;
+  Carver c(ws);
+  g.kp = (int64_t)align_up((size_t)n_tok, 64);
+  g.wmax = c.take<float>(1);
+  g.e = c.take<int>((size_t)c_in);
+  g.xst = c.take<uint16_t>((size_t)c_in * g.kp);
+  g.H = c.take<float>((size_t)c_in * c_in);
+  g.bytes = c.off;
+  return g;
+}
+struct GramSearchPlan { float* s_table; float* inv_table; float* partial; uint16_t* dq; size_t bytes;
+                        int64_t tiles_o, tiles_t; };
+GramSearchPlan plan_gram_search(void* ws, int64_t c_in, int64_t c_out, int n_alpha) {
+  GramSearchPlan s;
+  Carver c(ws);
+  gemm_tile_counts(c_out, c_in, &s.tiles_o, &s.tiles_t);   // weight rows take the token role
+  s.s_table = c.take<float>((size_t)n_alpha * c_in);
+  s.inv_table = c.take<float>((size_t)n_alpha * c_in);
+  s.partial = c.take<float>((size_t)n_alpha * s.tiles_o * s.tiles_t);
+  s.dq = c.take<uint16_t>((size_t)n_alpha * c_out * c_in);
+  s.bytes = c.off;
+  return s;
+}
 }  // namespace
 
 extern "C" {
@@ -458,6 +495,87 @@ tlq_status tlq_prepare_tokens(const void* X, int64_t n_tok, int64_t c_in, int64_
   const Prepared v = view_prepared(prepared);
   return hip_status(launch_xprep(X, n_tok, c_in, ldx, const_cast<uint32_t*>(v.xmax), const_cast<uint16_t*>(v.xh),
                                  (hipStream_t)stream));
+}
+
+// ---------------------------------------- second-moment form of the weight-only search
+size_t tlq_token_gram_bytes(int64_t c_in) {
+  if (c_in <= 0) return 0;
+  return view_gram(nullptr, c_in).bytes;
+}
+
+size_t tlq_token_gram_workspace_bytes(int64_t n_tok, int64_t c_in) {
+  if (n_tok <= 0 || c_in <= 0) return 0;
+  return plan_gram(nullptr, n_tok, c_in).bytes;
+}
+
+tlq_status tlq_token_gram(const void* X, int64_t n_tok, int64_t c_in, int64_t ldx, const float* token_w,
+                          const tlq_params* p, void* gram, size_t gram_bytes, void* workspace,
+                          size_t workspace_bytes, void* stream) {
+  if (!X || !token_w) return TLQ_ERR_NULL;
+  TLQ_TRY(check_params(p));
+  if (!dims_ok(n_tok, c_in, ldx) || (c_in % 8) != 0) return TLQ_ERR_SHAPE;
+  if (!mat16_aligned(X, ldx) || !aligned(token_w, 4)) return TLQ_ERR_ALIGN;
+  if (!gram || gram_bytes < tlq_token_gram_bytes(c_in)) return TLQ_ERR_WORKSPACE;
+  if (!aligned(gram, 256)) return TLQ_ERR_ALIGN;
+  TLQ_TRY(check_ws(workspace, workspace_bytes, tlq_token_gram_workspace_bytes(n_tok, c_in)));
+  hipStream_t st = (hipStream_t)stream;
+  const GramView v = view_gram(gram, c_in);
+  const GramPlan g = plan_gram(workspace, n_tok, c_in);
+  TLQ_HIP(launch_gram_operand(X, n_tok, c_in, ldx, p->x_dtype == TLQ_BF16, token_w, g.wmax, g.xst, g.kp, st));
+  // H[j, i] = sum_t xs[i, t] xs[j, t]: both operands are the transposed tokens, contraction over t
+  GemmArgs r{};
+  r.X = g.xst; r.n_tok = c_in; r.c_in = g.kp; r.ldx = g.kp;
+  r.Wh = g.xst; r.c_out = c_in; r.ldw = g.kp; r.w_cand_stride = 0; r.n_cand = 1; r.bf16 = false;
+  r.Yout = g.H; r.ldo = c_in; r.yout_dtype = TLQ_F32; r.tri = true;
+  TLQ_HIP(launch_gemm_store(r, st));
+  return hip_status(launch_gram_finish(g.H, c_in, g.wmax, g.e, v.factor, v.col_scale, v.C, st));
+}
+
+size_t tlq_scale_search_gram_workspace_bytes(int64_t c_in, int64_t c_out, int32_t n_alpha,
+                                             const tlq_params* p) {
+  if (c_in <= 0 || c_out <= 0 || n_alpha <= 0 || n_alpha > TLQ_MAX_ALPHA || check_params(p) != TLQ_OK)
+    return 0;
+  return plan_gram_search(nullptr, c_in, c_out, n_alpha).bytes;
+}
+
+tlq_status tlq_scale_search_gram(const void* gram, int64_t c_in, const void* W, int64_t c_out, int64_t ldw,
+                                 const float* alpha_grid, int32_t n_alpha, const tlq_params* p,
+                                 const float* x_stat, float* best_scales, int32_t* best_idx, float* losses,
+                                 float* s_table_out, void* workspace, size_t workspace_bytes, void* stream) {
+  if (!gram || !W || !alpha_grid || !x_stat || !best_scales || !best_idx || !losses) return TLQ_ERR_NULL;
+  TLQ_TRY(check_params(p));
+  if (p->act_bits != 0) return TLQ_ERR_UNSUPPORTED;   // Q_a makes f_q non-linear in the tokens
+  if (n_alpha <= 0 || n_alpha > TLQ_MAX_ALPHA) return TLQ_ERR_SHAPE;
+  if (!dims_ok(c_out, c_in, ldw)) return TLQ_ERR_SHAPE;
+  TLQ_TRY(check_cin(c_in, p));
+  if (!mat16_aligned(W, ldw) || !aligned(gram, 256)) return TLQ_ERR_ALIGN;
+  TLQ_TRY(check_ws(workspace, workspace_bytes,
+                   tlq_scale_search_gram_workspace_bytes(c_in, c_out, n_alpha, p)));
+  hipStream_t st = (hipStream_t)stream;
+  const GramView v = view_gram(const_cast<void*>(gram), c_in);
+  const GramSearchPlan s = plan_gram_search(workspace, c_in, c_out, n_alpha);
+  TLQ_HIP(launch_scale_table(x_stat, c_in, alpha_grid, n_alpha, s.s_table, s.inv_table, nullptr, st));
+  if (s_table_out)
+    TLQ_HIP(hipMemcpyAsync(s_table_out, s.s_table, (size_t)n_alpha * c_in * sizeof(float),
+                           hipMemcpyDeviceToDevice, st));
+  // D'_k = (deq_k / s_k - W) * col_scale for every candidate, fp16
+  QuantArgs q{};
+  q.W = W; q.c_out = c_out; q.c_in = c_in; q.ldw = ldw; q.bf16 = p->x_dtype == TLQ_BF16;
+  q.bits = p->bits; q.group = p->group; q.symmetric = p->symmetric;
+  q.s_table = s.s_table; q.inv_table = s.inv_table; q.n_cand = n_alpha;
+  q.what = s.dq; q.what_cand_stride = c_out * c_in; q.what_f16 = true;
+  q.diff = true; q.xmax_bits = nullptr; q.col_scale = v.col_scale;
+  TLQ_HIP(launch_fake_quant(q, st));
+  // partial = sum_{o,i} (D'_k C)[o,i] D'_k[o,i]: the weight rows play the tokens, C the weights
+  GemmArgs g{};
+  g.X = s.dq; g.n_tok = c_out; g.c_in = c_in; g.ldx = c_in; g.x_cand_stride = c_out * c_in;
+  g.Wh = v.C; g.c_out = c_in; g.ldw = c_in; g.w_cand_stride = 0; g.n_cand = n_alpha; g.bf16 = false;
+  g.Yref = s.dq; g.ldy = c_in; g.yref_dtype = TLQ_F16; g.y_cand_stride = c_out * c_in;
+  g.partial = s.partial;
+  TLQ_HIP(launch_gemm_dot(g, st));
+  TLQ_HIP(launch_finalize(s.partial, n_alpha, s.tiles_o * s.tiles_t, c_out, s.s_table, c_in, losses,
+                          best_idx, best_scales, st, v.factor));
+  return TLQ_OK;
 }
 
 // ---------------------------------------------------------------- f_fp output

@@ -95,6 +95,7 @@ struct QuantArgs {
   uint8_t* codes; uint8_t* zp; float* delta; void* wdq; int64_t ld_dq;
   // difference form: `what` receives deq*inv - W*2^shift (shift from xmax_bits, 0 when NULL)
   bool diff; const uint32_t* xmax_bits;
+  const float* col_scale;   // [c_in] factor applied to `what` after everything else, or NULL
 };
 hipError_t launch_fake_quant(const QuantArgs& a, hipStream_t stream);
 
@@ -120,6 +121,8 @@ struct GemmArgs {
   int64_t w_cand_stride; int n_cand; bool bf16;
   // loss epilogue
   const void* Yref; int64_t ldy; int yref_dtype; const float* token_w;
+  int64_t y_cand_stride;   // launch_gemm_dot: elements between per-candidate Y matrices
+  bool tri;                // launch_gemm_store of a symmetric product (X == Wh): tiles with tile row <= tile column only
   float* partial;          // [n_cand, tiles_o, tiles_t] float
   float* tok_partial;      // [tiles_o, n_tok] float or NULL (single candidate only)
   // store epilogue (n_cand == 1): Y[t,o]
@@ -129,15 +132,28 @@ void gemm_tile_counts(int64_t n_tok, int64_t c_out, int64_t* tiles_o, int64_t* t
 int64_t tile_map_defects(int64_t n_tok, int64_t c_in, int64_t c_out, int n_cand, int64_t* blocks_out);
 hipError_t launch_gemm_loss(const GemmArgs& a, hipStream_t stream);
 hipError_t launch_gemm_store(const GemmArgs& a, hipStream_t stream);
+// partial[k, tile] = sum over the tile of (X_k Wh^T)[t,o] * Y_k[t,o]  (no token weights)
+hipError_t launch_gemm_dot(const GemmArgs& a, hipStream_t stream);
+
+// Second-moment form (gram.hip).  out[c, t] = fp16(X[t,c] * sqrt(w_t / max w)) as [c_in, kp] with zero
+// columns for n_tok <= t < kp; *wmax receives max_t w_t.
+hipError_t launch_gram_operand(const void* X, int64_t n_tok, int64_t c_in, int64_t ldx, bool bf16,
+                               const float* token_w, float* wmax, void* out, int64_t kp, hipStream_t stream);
+// H: float [c_in, c_in] product of that operand with itself (tiles with column tile <= row tile).
+// Writes the balanced fp16 matrix C, the per-channel factors of the weight errors and the factor
+// that turns d'^T C d' into the loss; e is scratch [c_in].
+hipError_t launch_gram_finish(const float* H, int64_t c_in, const float* wmax, int* e, double* factor,
+                              float* col_scale, void* C, hipStream_t stream);
 
 // D[t,o] = Y[t,o] - D[t,o] (D float, row stride ldd)
 hipError_t launch_sub_from_y(const void* Y, int64_t ldy, int ydt, float* D, int64_t ldd, int64_t n_tok,
                              int64_t c_out, hipStream_t stream);
 
 // S4 final combine + S5 selection.
+// `factor` (optional): device double multiplied into every loss
 hipError_t launch_finalize(const float* partial, int n_cand, int64_t tiles_per_cand, int64_t c_out,
                            const float* s_table, int64_t c_in, float* losses, int32_t* best_idx,
-                           float* best_scales, hipStream_t stream);
+                           float* best_scales, hipStream_t stream, const double* factor = nullptr);
 hipError_t launch_token_err_reduce(const float* tok_partial, int64_t tiles_o, int64_t n_tok,
                                    int64_t c_out, float* per_token_err, hipStream_t stream);
 

@@ -94,7 +94,9 @@ template <int IA, int JB> struct Acc16 {   // acc[IA][JB] of f32x4 (16x16x32)
   }
 };
 
-enum { EPI_LOSS = 0, EPI_LOSS_TOK = 1, EPI_STORE = 2 };
+// EPI_DOT: partial = sum over the tile of acc * Y (Y read like Y_ref, one matrix per candidate, no
+// token weights): the quadratic form of the second-moment search.
+enum { EPI_LOSS = 0, EPI_LOSS_TOK = 1, EPI_STORE = 2, EPI_DOT = 3 };
 constexpr int BK = 64;        // halves per k-tile
 constexpr int ROWB = BK * 2;  // bytes per LDS row
 constexpr int PATCH_O = 4, PATCH_T = 8;  // tiles per L2 patch (one patch per XCD at a time)
@@ -104,6 +106,8 @@ struct GemmDev {
   const float* tok_scale;  // [n_cand, n_tok] per-token factor on the accumulators, or NULL
   const uint16_t* Wh; int64_t c_out, ldw, w_cand_stride; int n_cand;
   const void* Yref; int64_t ldy; int ydt; const float* token_w;
+  int64_t y_cand_stride;   // elements between per-candidate Y matrices (EPI_DOT; 0 = shared)
+  int tri;                 // 1: only tiles with tile row <= tile column are computed (symmetric product)
   float* partial; float* tok_partial;
   void* Yout; int64_t ldo; int odt;
   int tiles_o, tiles_t, npo, npt;  // tiles per candidate and patches per candidate
@@ -158,8 +162,9 @@ __device__ __forceinline__ void store_y1(void* Y, int odt, int64_t idx, float y)
 // token is `tw`: sq[tb] = sum over this lane's rows of (Y_ref - acc)^2 for its token of
 // token block tb; part = sum_tb token_w * sq[tb].  YDT >= 0 fixes the Y_ref type at
 // compile time; FULL promises that the whole wave tile lies inside the matrix.
-template <int YDT, bool FULL, typename L, typename Acc>
-__device__ __forceinline__ void loss_rows(const GemmDev& a, const Acc& acc, const float* tsc,
+// DOT replaces the squared residual by the product acc * y and drops the token weight.
+template <int YDT, bool FULL, bool DOT, typename L, typename Acc>
+__device__ __forceinline__ void loss_rows(const GemmDev& a, const void* Yref, const Acc& acc, const float* tsc,
                                           int64_t ow, int64_t tw, float (&sq)[L::NTB], float& part) {
   const int lane = threadIdx.x & 63;
   const int ydt = YDT >= 0 ? YDT : a.ydt;
@@ -175,9 +180,10 @@ __device__ __forceinline__ void loss_rows(const GemmDev& a, const Acc& acc, cons
         const int64_t o = ow + L::row(q, lane);
         if (FULL || o + 3 < a.c_out) {
           float y[4];
-          load_y4(a.Yref, ydt, t * a.ldy + o, y);
+          load_y4(Yref, ydt, t * a.ldy + o, y);
 #pragma unroll
           for (int r = 0; r < 4; ++r) {
+            if (DOT) { sumsq += L::get(acc, q, tb, r) * y[r]; continue; }
             const float d = __builtin_fmaf(nsg, L::get(acc, q, tb, r), y[r]);
             sumsq += d * d;
           }
@@ -185,12 +191,14 @@ __device__ __forceinline__ void loss_rows(const GemmDev& a, const Acc& acc, cons
 #pragma unroll
           for (int r = 0; r < 4; ++r)
             if (o + r < a.c_out) {
-              const float d = __builtin_fmaf(nsg, L::get(acc, q, tb, r), load_y(a.Yref, ydt, t * a.ldy + o + r));
+              const float y = load_y(Yref, ydt, t * a.ldy + o + r);
+              if (DOT) { sumsq += L::get(acc, q, tb, r) * y; continue; }
+              const float d = __builtin_fmaf(nsg, L::get(acc, q, tb, r), y);
               sumsq += d * d;
             }
         }
       }
-      part += a.token_w[t] * sumsq;
+      part += DOT ? sumsq : a.token_w[t] * sumsq;
     }
     sq[tb] = sumsq;
   }
@@ -202,8 +210,8 @@ __device__ __forceinline__ void loss_rows(const GemmDev& a, const Acc& acc, cons
 // then every lane picks its values from there.  Reading Y_ref straight from the accumulator
 // layout touches 16 or 32 lines per instruction and each line 8 times.  16-byte chunks of a token
 // row are stored at chunk ^ (token % 16), which makes the 8-byte reads conflict-free.
-template <typename YT, typename L, typename Acc>
-__device__ __forceinline__ void loss_rows_lds(const GemmDev& a, const Acc& acc, const float* tsc,
+template <typename YT, bool DOT, typename L, typename Acc>
+__device__ __forceinline__ void loss_rows_lds(const GemmDev& a, const void* Yref, const Acc& acc, const float* tsc,
                                               int64_t ow, int64_t tw, float (&sq)[L::NTB], float& part,
                                               unsigned char* ylds) {
   constexpr int WO = L::WO, WT = L::WT;
@@ -211,7 +219,7 @@ __device__ __forceinline__ void loss_rows_lds(const GemmDev& a, const Acc& acc, 
   constexpr int RPI = 64 / CPR;            // token rows per wave-wide copy
   static_assert(CPR == 16 && WT % RPI == 0, "copy shape");
   const int lane = threadIdx.x & 63;
-  const uint16_t* Y = (const uint16_t*)a.Yref;
+  const uint16_t* Y = (const uint16_t*)Yref;
   {
     const int cr = lane / CPR, cc = lane % CPR;
     uint4 v[WT / RPI];
@@ -245,11 +253,12 @@ __device__ __forceinline__ void loss_rows_lds(const GemmDev& a, const Acc& acc, 
                           YT::to_float((uint16_t)(u.y & 0xffffu)), YT::to_float((uint16_t)(u.y >> 16))};
 #pragma unroll
       for (int r = 0; r < 4; ++r) {
+        if (DOT) { sumsq += L::get(acc, q, tb, r) * y[r]; continue; }
         const float d = __builtin_fmaf(nsg, L::get(acc, q, tb, r), y[r]);
         sumsq += d * d;
       }
     }
-    part += a.token_w[t] * sumsq;
+    part += DOT ? sumsq : a.token_w[t] * sumsq;
     sq[tb] = sumsq;
   }
 }
@@ -338,20 +347,23 @@ __device__ __forceinline__ void tile_epilogue(const GemmDev& a, const Acc& acc, 
   float sq[L::NTB];
   const bool interior = (o0 + NWO * WO <= a.c_out) && (t0 + BT <= a.n_tok);
   const int64_t ow = o0 + wo * WO, tw = t0 + wt * WT;
+  constexpr bool DOT = EPI == EPI_DOT;
+  const void* Yc = a.Yref;
+  if (DOT) Yc = (const unsigned char*)a.Yref + (int64_t)cand * a.y_cand_stride * (a.ydt == TLQ_F32 ? 4 : 2);
   bool done = false;
-  if constexpr (YLDS && EPI == EPI_LOSS) {
-    if (interior && a.ydt != TLQ_F32 && (a.ldy % 8) == 0 && ((uintptr_t)a.Yref % 16) == 0) {
+  if constexpr (YLDS && (EPI == EPI_LOSS || DOT)) {
+    if (interior && a.ydt != TLQ_F32 && (a.ldy % 8) == 0 && ((uintptr_t)Yc % 16) == 0) {
       unsigned char* ylds = reinterpret_cast<unsigned char*>(rows) + wave * (WO * WT * 2);
-      if (a.ydt == TLQ_F16) loss_rows_lds<F16, L>(a, acc, tsc, ow, tw, sq, part, ylds);
-      else loss_rows_lds<BF16, L>(a, acc, tsc, ow, tw, sq, part, ylds);
+      if (a.ydt == TLQ_F16) loss_rows_lds<F16, DOT, L>(a, Yc, acc, tsc, ow, tw, sq, part, ylds);
+      else loss_rows_lds<BF16, DOT, L>(a, Yc, acc, tsc, ow, tw, sq, part, ylds);
       done = true;
     }
   }
   if (done) {}
-  else if (interior && a.ydt == TLQ_F16) loss_rows<TLQ_F16, true, L>(a, acc, tsc, ow, tw, sq, part);
-  else if (interior && a.ydt == TLQ_F32) loss_rows<TLQ_F32, true, L>(a, acc, tsc, ow, tw, sq, part);
-  else if (interior) loss_rows<TLQ_BF16, true, L>(a, acc, tsc, ow, tw, sq, part);
-  else loss_rows<-1, false, L>(a, acc, tsc, ow, tw, sq, part);
+  else if (interior && a.ydt == TLQ_F16) loss_rows<TLQ_F16, true, DOT, L>(a, Yc, acc, tsc, ow, tw, sq, part);
+  else if (interior && a.ydt == TLQ_F32) loss_rows<TLQ_F32, true, DOT, L>(a, Yc, acc, tsc, ow, tw, sq, part);
+  else if (interior) loss_rows<TLQ_BF16, true, DOT, L>(a, Yc, acc, tsc, ow, tw, sq, part);
+  else loss_rows<-1, false, DOT, L>(a, Yc, acc, tsc, ow, tw, sq, part);
   if (EPI == EPI_LOSS_TOK) {
 #pragma unroll
     for (int tb = 0; tb < L::NTB; ++tb) {
@@ -435,6 +447,7 @@ __global__ __launch_bounds__((BO / WO) * (BT / WT) * 64) void gemm_kernel(GemmDe
 
   int cand, to, tt;
   if (!decode_tile(a, blockIdx.x, cand, to, tt)) return;
+  if (a.tri && to > tt) return;   // the mirrored tile carries the same values
   const int64_t o0 = (int64_t)to * BO, t0 = (int64_t)tt * BT;
 
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
@@ -613,6 +626,7 @@ __global__ __launch_bounds__(512) void gemm_dma_kernel(GemmDev a) {
 
   int cand, to, tt;
   if (!decode_tile(a, blockIdx.x, cand, to, tt)) return;
+  if (a.tri && to > tt) return;   // the mirrored tile carries the same values
   const int64_t o0 = (int64_t)to * BO, t0 = (int64_t)tt * BT;
 
   const int tid = threadIdx.x, lane = tid & 63;
@@ -781,6 +795,7 @@ static GemmDev make_dev(const GemmArgs& g) {
   d.Wh = (const uint16_t*)g.Wh; d.c_out = g.c_out; d.ldw = g.ldw;
   d.w_cand_stride = g.w_cand_stride; d.n_cand = g.n_cand;
   d.Yref = g.Yref; d.ldy = g.ldy; d.ydt = g.yref_dtype; d.token_w = g.token_w;
+  d.y_cand_stride = g.y_cand_stride; d.tri = g.tri ? 1 : 0;
   d.partial = g.partial; d.tok_partial = g.tok_partial;
   d.Yout = g.Yout; d.ldo = g.ldo; d.odt = g.yout_dtype;
   int64_t to, tt;
@@ -820,7 +835,9 @@ static hipError_t launch_gemm(const GemmArgs& g, const char* name, hipStream_t s
   const int64_t rounds = ceil_div(d.n_patches, 8);
   const int64_t blocks = rounds * 8 * PATCH_O * PATCH_T;
   if (blocks > 0x7fffffffLL) return hipErrorInvalidValue;
-  ProfScope ps(name, stream, 2.0 * (double)g.n_tok * (double)g.c_in * (double)g.c_out * g.n_cand);
+  // (a symmetric product computes the tiles on and above the diagonal: about half)
+  const double tile_frac = g.tri ? 0.5 * (1.0 + 1.0 / (double)d.tiles_o) : 1.0;
+  ProfScope ps(name, stream, 2.0 * (double)g.n_tok * (double)g.c_in * (double)g.c_out * g.n_cand * tile_frac);
   constexpr int NT = (kBO / kWO) * (kBT / kWT) * 64;
   // the pipelined kernel needs whole k-tiles and 32-bit byte offsets inside a 256-row panel
   const bool dma = (g.c_in % kDmaBK) == 0 && g.ldw < (1 << 21) && g.ldx < (1 << 21);
@@ -868,7 +885,11 @@ hipError_t launch_gemm_loss(const GemmArgs& g, hipStream_t stream) {
   return launch_gemm<EPI_LOSS>(g, "gemm_loss", stream);
 }
 hipError_t launch_gemm_store(const GemmArgs& g, hipStream_t stream) {
-  return launch_gemm<EPI_STORE>(g, "gemm_store", stream);
+  if (g.tri && (g.n_tok != g.c_out || g.n_cand != 1)) return hipErrorInvalidValue;
+  return launch_gemm<EPI_STORE>(g, g.tri ? "gemm_gram" : "gemm_store", stream);
+}
+hipError_t launch_gemm_dot(const GemmArgs& g, hipStream_t stream) {
+  return launch_gemm<EPI_DOT>(g, "gemm_gram_loss", stream);
 }
 
 }  // namespace tlq

@@ -22,6 +22,7 @@ struct QuantDev {
   uint16_t* what; int64_t what_cand_stride; bool what_f16;
   uint8_t* codes; uint8_t* zp; float* delta; uint16_t* wdq; int64_t ld_dq;
   bool diff; const uint32_t* xmax_bits;  // what = deq*inv - W*2^shift
+  const float* col_scale;                // [c_in] factor on `what` or NULL
 };
 
 template <bool SYM>
@@ -96,6 +97,15 @@ __global__ __launch_bounds__(256) void quant_pow2_kernel(QuantDev a) {
   const int64_t gidx = row * (a.c_in / a.group) + c / a.group;
 
   const float wsub = a.diff ? (a.xmax_bits ? __builtin_ldexpf(1.0f, shift_from_bf16_bits(*a.xmax_bits)) : 1.0f) : 0.0f;
+  float cs[8];
+#pragma unroll
+  for (int j = 0; j < 8; ++j) cs[j] = 1.0f;
+  if (active && a.col_scale) {
+    const float4 c0 = *reinterpret_cast<const float4*>(a.col_scale + c);
+    const float4 c1 = *reinterpret_cast<const float4*>(a.col_scale + c + 4);
+    cs[0] = c0.x; cs[1] = c0.y; cs[2] = c0.z; cs[3] = c0.w;
+    cs[4] = c1.x; cs[5] = c1.y; cs[6] = c1.z; cs[7] = c1.w;
+  }
   for (int k = 0; k < a.n_cand; ++k) {
     float s[8], inv[8];
 #pragma unroll
@@ -141,6 +151,7 @@ __global__ __launch_bounds__(256) void quant_pow2_kernel(QuantDev a) {
       quant_one<SYM>(ws[j], delta, rdelta, zpf, a, code, deq);
       float folded = deq * inv[j];
       if (a.diff) folded -= w[j] * wsub;
+      if (a.col_scale) folded *= cs[j];
       hw[j >> 1] |= (uint32_t)(a.what_f16 ? F16::from_float(folded) : T::from_float(folded)) << ((j & 1) * 16);
       if (AUX) {
         cw[j >> 2] |= ((uint32_t)code & 0xffu) << ((j & 3) * 8);
@@ -198,6 +209,7 @@ __global__ __launch_bounds__(256) void quant_any_kernel(QuantDev a) {
         {
           float folded = deq * (ik ? ik[c] : 1.0f);
           if (a.diff) folded -= T::to_float(a.W[row * a.ldw + c]) * wsub;
+          if (a.col_scale) folded *= a.col_scale[c];
           a.what[(int64_t)k * a.what_cand_stride + row * a.c_in + c] =
               a.what_f16 ? F16::from_float(folded) : T::from_float(folded);
         }
@@ -349,7 +361,7 @@ hipError_t launch_fake_quant(const QuantArgs& q, hipStream_t stream) {
   d.s_table = q.s_table; d.inv_table = q.inv_table; d.n_cand = q.n_cand;
   d.what = (uint16_t*)q.what; d.what_cand_stride = q.what_cand_stride; d.what_f16 = q.what_f16;
   d.codes = q.codes; d.zp = q.zp; d.delta = q.delta; d.wdq = (uint16_t*)q.wdq; d.ld_dq = q.ld_dq;
-  d.diff = q.diff; d.xmax_bits = q.xmax_bits;
+  d.diff = q.diff; d.xmax_bits = q.xmax_bits; d.col_scale = q.col_scale;
   const bool pow2 = d.group >= 8 && d.group <= 512 && (d.group & (d.group - 1)) == 0;
   const double bytes = (double)q.c_out * (double)q.c_in * (2.0 + 2.0 * (q.what ? q.n_cand : 0) +
                                                            (q.codes ? 1.0 : 0.0) + (q.wdq ? 2.0 : 0.0));

@@ -211,7 +211,7 @@ hipError_t launch_xprep(const void* X, int64_t n_tok, int64_t c_in, int64_t ldx,
 // minimum (Sec. 3.2.1 argmin) and the block copies that row of the table.
 __global__ __launch_bounds__(1024) void finalize_kernel(
     const float* __restrict__ partial, int n_cand, int64_t tiles_per_cand, double inv_c_out,
-    const float* __restrict__ s_table, int64_t c_in, float* __restrict__ losses,
+    const double* __restrict__ factor, const float* __restrict__ s_table, int64_t c_in, float* __restrict__ losses,
     int32_t* __restrict__ best_idx, float* __restrict__ best_scales) {
   __shared__ float sl[TLQ_MAX_ALPHA];
   __shared__ int sbest;
@@ -223,7 +223,7 @@ __global__ __launch_bounds__(1024) void finalize_kernel(
 #pragma unroll
     for (int off = 32; off >= 1; off >>= 1) acc += __shfl_xor(acc, off, 64);
     if (lane == 0) {
-      float l = (float)(acc * inv_c_out);
+      float l = (float)(acc * inv_c_out * (factor ? *factor : 1.0));
       if (!(l == l) || l == __builtin_inff() || l == -__builtin_inff()) l = __builtin_inff();
       sl[k] = l;
       losses[k] = l;
@@ -248,10 +248,10 @@ __global__ __launch_bounds__(1024) void finalize_kernel(
 
 hipError_t launch_finalize(const float* partial, int n_cand, int64_t tiles_per_cand, int64_t c_out,
                            const float* s_table, int64_t c_in, float* losses, int32_t* best_idx,
-                           float* best_scales, hipStream_t stream) {
+                           float* best_scales, hipStream_t stream, const double* factor) {
   ProfScope ps("finalize", stream, 4.0 * (double)n_cand * (double)tiles_per_cand);
   finalize_kernel<<<1, 1024, 0, stream>>>(partial, n_cand, tiles_per_cand, 1.0 / (double)c_out,
-                                          s_table, c_in, losses, best_idx, best_scales);
+                                          factor, s_table, c_in, losses, best_idx, best_scales);
   return hipGetLastError();
 }
 

@@ -67,6 +67,11 @@ _SIGNATURES = {
     "tlq_scale_search_prepared": (C.c_int, [_P, _I64, _I64, _I64, _P, _I64, _I64, _P, _I64, _P, _P, _I32,
                                             _PP, _P, _P, _P, _P, _P, _P, _SZ, _P, _P]),
     "tlq_apply_best_prepared": (C.c_int, [_P, _I64, _I64, _I64, _P, _I64, _I64, _P, _PP, _P, _I64, _P, _SZ, _P, _P]),
+    "tlq_token_gram_bytes": (_SZ, [_I64]),
+    "tlq_token_gram_workspace_bytes": (_SZ, [_I64, _I64]),
+    "tlq_token_gram": (C.c_int, [_P, _I64, _I64, _I64, _P, _PP, _P, _SZ, _P, _SZ, _P]),
+    "tlq_scale_search_gram_workspace_bytes": (_SZ, [_I64, _I64, _I32, _PP]),
+    "tlq_scale_search_gram": (C.c_int, [_P, _I64, _P, _I64, _I64, _P, _I32, _PP, _P, _P, _P, _P, _P, _P, _SZ, _P]),
     "tlq_ref_output": (C.c_int, [_P, _I64, _I64, _I64, _P, _I64, _I64, _P, _I64, _PP, _P]),
     "tlq_apply_best_workspace_bytes": (_SZ, [_I64, _I64, _I64, _PP]),
     "tlq_apply_best": (C.c_int, [_P, _I64, _I64, _I64, _P, _I64, _I64, _P, _PP, _P, _I64, _P, _SZ, _P]),
@@ -252,6 +257,50 @@ def scale_search(X, W, Y_ref, token_w, alpha_grid, p, best_scales, best_idx, los
                                                _ptr(x_stat_in), _ptr(best_scales), _ptr(best_idx), _ptr(losses),
                                                _ptr(s_table_out), _ptr(ws), ws.numel(), _stream(), _ptr(prepared)),
                "tlq_scale_search_prepared")
+
+
+def token_gram_bytes(c_in):
+    return int(lib().tlq_token_gram_bytes(c_in))
+
+
+def token_gram_workspace_bytes(n_tok, c_in):
+    return int(lib().tlq_token_gram_workspace_bytes(n_tok, c_in))
+
+
+def token_gram(X, token_w, p, gram, workspace=None):
+    """Fill `gram` (uint8 tensor of token_gram_bytes(c_in) bytes) with the weighted second-moment
+    matrix of the tokens; see tlq.h."""
+    n, ci = X.shape
+    ws = workspace if workspace is not None else _ws(token_gram_workspace_bytes(n, ci), X)
+    _check(lib().tlq_token_gram(_ptr(X), n, ci, _ld(X), _ptr(token_w), C.byref(p), _ptr(gram),
+                                0 if gram is None else gram.numel(), _ptr(ws), ws.numel(), _stream()),
+           "tlq_token_gram")
+    return gram
+
+
+def gram_views(gram, c_in):
+    """(factor [1] f64, col_scale [c_in] f32, C [c_in, c_in] f16) views of a filled gram buffer:
+    G[i, j] = factor * col_scale[i] * col_scale[j] * C[i, j]."""
+    import torch
+    a256 = lambda n: (n + 255) // 256 * 256
+    o1, o2 = 256, 256 + a256(4 * c_in)
+    return (gram[:8].view(torch.float64), gram[o1:o1 + 4 * c_in].view(torch.float32),
+            gram[o2:o2 + 2 * c_in * c_in].view(torch.float16).view(c_in, c_in))
+
+
+def scale_search_gram_workspace_bytes(c_in, c_out, n_alpha, p):
+    return int(lib().tlq_scale_search_gram_workspace_bytes(c_in, c_out, n_alpha, C.byref(p)))
+
+
+def scale_search_gram(gram, W, alpha_grid, p, x_stat, best_scales, best_idx, losses,
+                      s_table_out=None, workspace=None):
+    co, ci = W.shape
+    na = alpha_grid.numel()
+    ws = workspace if workspace is not None else _ws(scale_search_gram_workspace_bytes(ci, co, na, p), W)
+    _check(lib().tlq_scale_search_gram(_ptr(gram), ci, _ptr(W), co, _ld(W), _ptr(alpha_grid), na, C.byref(p),
+                                       _ptr(x_stat), _ptr(best_scales), _ptr(best_idx), _ptr(losses),
+                                       _ptr(s_table_out), _ptr(ws), ws.numel(), _stream()),
+           "tlq_scale_search_gram")
 
 
 def ref_output(X, W, Y, p):

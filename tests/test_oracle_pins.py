@@ -457,3 +457,44 @@ def test_brute_force_random_tiny_layers():
         assert res["best_idx"] == int(np.argmin(res["losses"]))
 
     run()
+
+
+def test_token_second_moment_pins():
+    """The second-moment matrix against what fixes it: explicit loops on a tiny case, symmetry and
+    positive semi-definiteness, the closed form for one-hot tokens, and the identity that ties it
+    to the (brute-force pinned) weighted layer error - the loss of f_q(x) = What x against
+    f_fp(x) = W x is the quadratic form of W - What in it."""
+    rng = np.random.default_rng(11)
+    n, ci, co = 13, 6, 5
+    X = rng.standard_normal((n, ci)).astype(np.float16)
+    w = rng.uniform(0.1, 1.0, n)
+    w = (w / w.sum()).astype(np.float32)
+    G = orc.token_second_moment(X, w)
+    loops = np.zeros((ci, ci))
+    for t in range(n):
+        for i in range(ci):
+            for j in range(ci):
+                loops[i, j] += float(w[t]) * float(X[t, i]) * float(X[t, j])
+    np.testing.assert_allclose(G, loops, rtol=1e-13, atol=1e-15)
+    assert np.array_equal(G, G.T) or np.allclose(G, G.T, rtol=1e-15)
+    assert np.linalg.eigvalsh(G).min() > -1e-12
+    np.testing.assert_allclose(orc.token_second_moment(X, w, rows=[4, 1], cols=[0, 5, 2]), G[np.ix_([4, 1], [0, 5, 2])],
+                               rtol=1e-13)
+    # one-hot tokens: G is diagonal with the weight mass of each channel
+    E = np.eye(ci, dtype=np.float16)[rng.integers(0, ci, n)]
+    Gd = orc.token_second_moment(E, w)
+    want = np.zeros(ci)
+    for t in range(n):
+        want[int(np.argmax(E[t]))] += float(w[t])
+    np.testing.assert_allclose(Gd, np.diag(want), rtol=1e-13, atol=0)
+    # quadratic-form identity with the layer error (asymmetric in rows/columns and in the sign of
+    # the difference's cross terms, so a transposed or mis-weighted G fails it)
+    W = (rng.standard_normal((co, ci)) * 0.05).astype(np.float16)
+    s = orc.scale_table(orc.x_stat_mean(X), np.array([0.45], np.float32))[0]
+    _, _, _, deq = orc.fake_quant(W.astype(np.float32), s, 3, 2)
+    L, _ = orc.weighted_layer_err(X, deq, orc.ref_output(X, W), w, s=s)
+    D = W.astype(np.float64) - deq.astype(np.float64) / s.astype(np.float64)
+    np.testing.assert_allclose(np.einsum("oi,ij,oj->", D, G, D) / co, L, rtol=1e-11)
+    # and it does not hold for the transposed weighting (rows weighted instead of tokens)
+    Gbad = (X.astype(np.float64).T @ X.astype(np.float64)) / n
+    assert abs(np.einsum("oi,ij,oj->", D, Gbad, D) / co - L) > 1e-6 * L
