@@ -166,6 +166,55 @@ def timed_workload(wl, tlq, torch, workload, layers, p, al, workspace, steps, wa
     }
 
 
+def second_moment_leg(tlq, torch, workload, layers, p, al, steps, warmup):
+    """The same searches in the second-moment form (tlq_token_gram + tlq_scale_search_gram): one
+    step = for every linear its channel statistic, the weighted second-moment matrix of its
+    tokens and the 20-candidate search through it.  (A real layer shares the matrix between q/k/v
+    and between gate/up; here every linear has its own synthetic input, so each pays for its
+    own.)  Reported next to the headline, never as `value`: it does not run the tokens through
+    every candidate.  Its losses are compared with those of the token form on the same inputs."""
+    import numpy as np
+    dev = layers[0][1].device
+    n_tok = workload.n_tok
+    cmax = max(s.c_in for s in workload.linears)
+    gram = torch.empty(tlq.token_gram_bytes(cmax), dtype=torch.uint8, device=dev)
+    ws = torch.empty(max(max(tlq.token_gram_workspace_bytes(n_tok, s.c_in), tlq.x_stat_workspace_bytes(n_tok, s.c_in),
+                             tlq.scale_search_gram_workspace_bytes(s.c_in, s.c_out, workload.n_alpha, p))
+                         for s in workload.linears), dtype=torch.uint8, device=dev)
+    outs = [(torch.empty(s.c_in, dtype=torch.float32, device=dev), torch.empty_like(o[0]), torch.empty_like(o[1]),
+             torch.empty_like(o[2])) for s, _, _, _, _, o in layers]
+
+    def step():
+        for (spec, X, W, Y, w, _), (xs, best, idx, losses) in zip(layers, outs):
+            tlq.x_stat(X, p, xs, workspace=ws)
+            g = tlq.token_gram(X, w, p, gram[:tlq.token_gram_bytes(spec.c_in)], workspace=ws)
+            tlq.scale_search_gram(g, W, al, p, xs, best, idx, losses, workspace=ws)
+
+    for _ in range(warmup):
+        step()
+    torch.cuda.synchronize()
+    tlq.profile_reset()
+    tlq.profile_enable(True)
+    t0 = time.perf_counter()
+    for _ in range(steps):
+        step()
+    torch.cuda.synchronize()
+    dt = time.perf_counter() - t0
+    tlq.profile_enable(False)
+    kernels = {k.name: k for k in tlq.profile_read()}
+    rel, same = 0.0, True
+    for (_, _, _, _, _, (_, idx_t, l_t)), (_, _, idx_g, l_g) in zip(layers, outs):
+        a, b = l_t.cpu().numpy().astype(np.float64), l_g.cpu().numpy().astype(np.float64)
+        rel = max(rel, float(np.max(np.abs(a - b) / a)))
+        same = same and int(idx_t.item()) == int(idx_g.item())
+    return {"value": len(layers) * workload.n_alpha * steps / dt, "unit": "evals/s", "ms_per_step": dt / steps * 1e3,
+            "max_rel_vs_token_form": rel, "same_choices": same,
+            "kernels": {k.name: {"launches": k.launches, "ms": round(k.total_ms, 4),
+                                 "rate": (k.total_work / (k.total_ms * 1e-3) / 1e9) if k.total_ms > 0 else None,
+                                 "rate_unit": "GFLOP/s" if k.name.startswith("gemm") else "GB/s"}
+                        for k in kernels.values()}}
+
+
 def oracle_leg(wl, tlq, torch, orc, workload, dev, p, n_samples, cands, x_abs_sum):
     """The oracle, as it stands, timed on a bounded sample of the workload's first linear:
     the first `n_samples` calibration samples and the candidates `cands` of the grid, with the
@@ -241,6 +290,8 @@ def main():
                     help="headline workload; the default run also times cfg2_7b_w4 as a secondary block")
     ap.add_argument("--no-secondary", action="store_true", help="skip the secondary workload")
     ap.add_argument("--no-cpu-baseline", action="store_true", help="skip the oracle timing and parity legs")
+    ap.add_argument("--no-second-moment", action="store_true",
+                    help="skip the second-moment-form leg (the same searches through the token Gram matrix)")
     ap.add_argument("--no-ceiling", action="store_true",
                     help="skip the register-only MFMA ceiling measurement (context only)")
     args = ap.parse_args()
@@ -279,6 +330,10 @@ def main():
         res = timed_workload(wl, tlq, torch, workload, layers, p, al, workspace, args.steps, args.warmup,
                              args.act_bits)
         log(f"{name}: {res['value']:.1f} evals/s, gemm_loss {res['fused_kernel_tflops']:.1f} TFLOP/s")
+        if args.act_bits == 0 and not args.no_second_moment:
+            res["second_moment_form"] = second_moment_leg(tlq, torch, workload, layers, p, al, args.steps, args.warmup)
+            log(f"{name}: second-moment form {res['second_moment_form']['value']:.1f} evals/s, "
+                f"max rel vs token form {res['second_moment_form']['max_rel_vs_token_form']:.2e}")
         if oracle_on:
             from oracle import tlq_oracle as orc
             ns, cands = ORACLE_SAMPLE[name]
@@ -298,7 +353,7 @@ def main():
         "data": "synthetic",
     }
     for k in ("config", "fused_kernel_tflops", "pct_fp16_mfma_peak", "roofline", "cpu_baseline", "parity",
-              "kernels", "per_linear", "best_alpha_index"):
+              "kernels", "per_linear", "best_alpha_index", "second_moment_form"):
         if k in head:
             result[k] = head[k]
     if not args.no_secondary:

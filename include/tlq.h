@@ -327,8 +327,9 @@ tlq_status tlq_residual_add(const void* H, int64_t ldh, const void* Z, int64_t l
                             int64_t c, const tlq_params* p, void* Out, int64_t ldo, void* stream);
 
 /* ---- host-side self check (no GPU work, no device memory): walks the block -> tile map that
- * the contraction kernels (S3/S4, f_fp, S6) would use for this problem shape and returns how many
- * (candidate, output tile) pairs are NOT produced exactly once - 0 for a correct map, -1 for an
+ * the contraction kernels (S3/S4, f_fp, S6) would use for this problem shape, in both of its
+ * orders (candidates inside every patch row / candidate-outermost), and returns how many
+ * (candidate, output tile) pairs are NOT produced exactly once - 0 for correct maps, -1 for an
  * invalid shape.  *blocks (may be NULL) receives the number of workgroups of the launch. */
 int64_t tlq_selftest_tile_map(int64_t n_tok, int64_t c_in, int64_t c_out, int32_t n_cand,
                               int64_t* blocks);

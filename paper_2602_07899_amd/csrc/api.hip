@@ -144,15 +144,27 @@ GramView view_gram(void* buf, int64_t c_in) {
   v.bytes = c.off;
   return v;
 }
-struct GramPlan { float* wmax; int* e; uint16_t* xst; float* H; int64_t kp; size_t bytes; };
+// The token product has only (c_in / 256)^2 / 2 output tiles and a very long contraction: it is
+// split along the tokens into n_split partial products (summed afterwards in a fixed order) so
+// that the launch has a few thousand workgroups.
+struct GramPlan { float* wmax; int* e; uint16_t* xst; float* H; int64_t kp, kc; int n_split; size_t bytes; };
 GramPlan plan_gram(void* ws, int64_t n_tok, int64_t c_in) {
   GramPlan g;
   Carver c(ws);
-  g.kp = (int64_t)align_up((size_t)n_tok, 64);
+  int64_t to, tt;
+  gemm_tile_counts(c_in, c_in, &to, &tt);
+  const int64_t live = to * (to + 1) / 2;
+  int64_t ns = (2048 + live - 1) / live;
+  const int64_t max_ns = n_tok / 4096;                 // at least 4096 tokens (64 k-tiles) per split
+  ns = ns > 16 ? 16 : ns;
+  ns = ns > max_ns ? max_ns : ns;
+  g.n_split = (int)(ns < 1 ? 1 : ns);
+  g.kc = (int64_t)align_up((size_t)((n_tok + g.n_split - 1) / g.n_split), 64);
+  g.kp = g.kc * g.n_split;
   g.wmax = c.take<float>(1);
   g.e = c.take<int>((size_t)c_in);
   g.xst = c.take<uint16_t>((size_t)c_in * g.kp);
-  g.H = c.take<float>((size_t)c_in * c_in);
+  g.H = c.take<float>((size_t)g.n_split * c_in * c_in);
   g.bytes = c.off;
   return g;
 }
@@ -522,13 +534,16 @@ tlq_status tlq_token_gram(const void* X, int64_t n_tok, int64_t c_in, int64_t ld
   const GramView v = view_gram(gram, c_in);
   const GramPlan g = plan_gram(workspace, n_tok, c_in);
   TLQ_HIP(launch_gram_operand(X, n_tok, c_in, ldx, p->x_dtype == TLQ_BF16, token_w, g.wmax, g.xst, g.kp, st));
-  // H[j, i] = sum_t xs[i, t] xs[j, t]: both operands are the transposed tokens, contraction over t
+  // H_s[j, i] = sum over the tokens of split s of xs[i, t] xs[j, t]: both operands are the transposed
+  // tokens, the splits take the role of candidates (column ranges of the same matrix)
   GemmArgs r{};
-  r.X = g.xst; r.n_tok = c_in; r.c_in = g.kp; r.ldx = g.kp;
-  r.Wh = g.xst; r.c_out = c_in; r.ldw = g.kp; r.w_cand_stride = 0; r.n_cand = 1; r.bf16 = false;
-  r.Yout = g.H; r.ldo = c_in; r.yout_dtype = TLQ_F32; r.tri = true;
+  r.X = g.xst; r.n_tok = c_in; r.c_in = g.kc; r.ldx = g.kp; r.x_cand_stride = g.kc;
+  r.Wh = g.xst; r.c_out = c_in; r.ldw = g.kp; r.w_cand_stride = g.kc; r.n_cand = g.n_split; r.bf16 = false;
+  r.Yout = g.H; r.ldo = c_in; r.yout_dtype = TLQ_F32; r.o_cand_stride = c_in * c_in; r.tri = true;
+  r.cand_outer = true;
   TLQ_HIP(launch_gemm_store(r, st));
-  return hip_status(launch_gram_finish(g.H, c_in, g.wmax, g.e, v.factor, v.col_scale, v.C, st));
+  return hip_status(launch_gram_finish(g.H, c_in, g.n_split, c_in * c_in, g.wmax, g.e, v.factor, v.col_scale,
+                                       v.C, st));
 }
 
 size_t tlq_scale_search_gram_workspace_bytes(int64_t c_in, int64_t c_out, int32_t n_alpha,
@@ -571,7 +586,7 @@ tlq_status tlq_scale_search_gram(const void* gram, int64_t c_in, const void* W, 
   g.X = s.dq; g.n_tok = c_out; g.c_in = c_in; g.ldx = c_in; g.x_cand_stride = c_out * c_in;
   g.Wh = v.C; g.c_out = c_in; g.ldw = c_in; g.w_cand_stride = 0; g.n_cand = n_alpha; g.bf16 = false;
   g.Yref = s.dq; g.ldy = c_in; g.yref_dtype = TLQ_F16; g.y_cand_stride = c_out * c_in;
-  g.partial = s.partial;
+  g.partial = s.partial; g.cand_outer = true;   // D'_k and C stay cache-resident for one candidate at a time
   TLQ_HIP(launch_gemm_dot(g, st));
   TLQ_HIP(launch_finalize(s.partial, n_alpha, s.tiles_o * s.tiles_t, c_out, s.s_table, c_in, losses,
                           best_idx, best_scales, st, v.factor));

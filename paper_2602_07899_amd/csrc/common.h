@@ -123,6 +123,8 @@ struct GemmArgs {
   const void* Yref; int64_t ldy; int yref_dtype; const float* token_w;
   int64_t y_cand_stride;   // launch_gemm_dot: elements between per-candidate Y matrices
   bool tri;                // launch_gemm_store of a symmetric product (X == Wh): tiles with tile row <= tile column only
+  bool cand_outer;         // walk the candidates one after the other instead of inside every patch row
+  int64_t o_cand_stride;   // launch_gemm_store with n_cand > 1: elements between per-candidate outputs
   float* partial;          // [n_cand, tiles_o, tiles_t] float
   float* tok_partial;      // [tiles_o, n_tok] float or NULL (single candidate only)
   // store epilogue (n_cand == 1): Y[t,o]
@@ -139,11 +141,12 @@ hipError_t launch_gemm_dot(const GemmArgs& a, hipStream_t stream);
 // columns for n_tok <= t < kp; *wmax receives max_t w_t.
 hipError_t launch_gram_operand(const void* X, int64_t n_tok, int64_t c_in, int64_t ldx, bool bf16,
                                const float* token_w, float* wmax, void* out, int64_t kp, hipStream_t stream);
-// H: float [c_in, c_in] product of that operand with itself (tiles with column tile <= row tile).
-// Writes the balanced fp16 matrix C, the per-channel factors of the weight errors and the factor
-// that turns d'^T C d' into the loss; e is scratch [c_in].
-hipError_t launch_gram_finish(const float* H, int64_t c_in, const float* wmax, int* e, double* factor,
-                              float* col_scale, void* C, hipStream_t stream);
+// H: n_split float [c_in, c_in] partial products of that operand with itself (tiles with column
+// tile <= row tile), split_stride elements apart; they are summed into the first.  Writes the
+// balanced fp16 matrix C, the per-channel factors of the weight errors and the factor that turns
+// d'^T C d' into the loss; e is scratch [c_in].
+hipError_t launch_gram_finish(float* H, int64_t c_in, int n_split, int64_t split_stride, const float* wmax,
+                              int* e, double* factor, float* col_scale, void* C, hipStream_t stream);
 
 // D[t,o] = Y[t,o] - D[t,o] (D float, row stride ldd)
 hipError_t launch_sub_from_y(const void* Y, int64_t ldy, int ydt, float* D, int64_t ldd, int64_t n_tok,

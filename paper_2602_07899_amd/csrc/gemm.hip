@@ -108,6 +108,8 @@ struct GemmDev {
   const void* Yref; int64_t ldy; int ydt; const float* token_w;
   int64_t y_cand_stride;   // elements between per-candidate Y matrices (EPI_DOT; 0 = shared)
   int tri;                 // 1: only tiles with tile row <= tile column are computed (symmetric product)
+  int cand_outer;          // 1: the candidate is the outermost level of the block order
+  int64_t o_cand_stride;   // EPI_STORE: elements between per-candidate outputs
   float* partial; float* tok_partial;
   void* Yout; int64_t ldo; int odt;
   int tiles_o, tiles_t, npo, npt;  // tiles per candidate and patches per candidate
@@ -268,7 +270,7 @@ __device__ __forceinline__ void loss_rows_lds(const GemmDev& a, const void* Yref
 // as loss_rows_lds), then the wave writes whole 128-byte lines, 8 lines per instruction.
 // Storing straight from the accumulator layout writes 8-byte pieces of 16 or 32 lines per instruction.
 template <typename YT, typename L, typename Acc>
-__device__ __forceinline__ void store_rows_lds(const GemmDev& a, const Acc& acc, const float* tsc,
+__device__ __forceinline__ void store_rows_lds(const GemmDev& a, void* Yout, const Acc& acc, const float* tsc,
                                                int64_t ow, int64_t tw, unsigned char* ylds) {
   constexpr int WO = L::WO, WT = L::WT;
   constexpr int CPR = WO / 8, RPI = 64 / CPR;
@@ -287,7 +289,7 @@ __device__ __forceinline__ void store_rows_lds(const GemmDev& a, const Acc& acc,
       *reinterpret_cast<uint2*>(ylds + tok * (WO * 2) + (((o >> 3) ^ (tok & 15)) << 4) + ((o >> 2) & 1) * 8) = u;
     }
   }
-  uint16_t* Y = (uint16_t*)a.Yout;
+  uint16_t* Y = (uint16_t*)Yout;
   const int cr = lane / CPR, cc = lane % CPR;
   // whole lines are read back by OTHER lanes of this wave: order the LDS writes before the reads
   __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
@@ -314,12 +316,13 @@ __device__ __forceinline__ void tile_epilogue(const GemmDev& a, const Acc& acc, 
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const float* tsc = a.tok_scale ? a.tok_scale + (int64_t)cand * a.n_tok : nullptr;
   if (EPI == EPI_STORE) {
+    void* Yo = (unsigned char*)a.Yout + (int64_t)cand * a.o_cand_stride * (a.odt == TLQ_F32 ? 4 : 2);
     if constexpr (YLDS) {
       if (a.odt != TLQ_F32 && (o0 + NWO * WO <= a.c_out) && (t0 + BT <= a.n_tok) && (a.ldo % 8) == 0 &&
-          ((uintptr_t)a.Yout % 16) == 0) {
+          ((uintptr_t)Yo % 16) == 0) {
         unsigned char* ylds = reinterpret_cast<unsigned char*>(rows) + wave * (WO * WT * 2);
-        if (a.odt == TLQ_F16) store_rows_lds<F16, L>(a, acc, tsc, o0 + wo * WO, t0 + wt * WT, ylds);
-        else store_rows_lds<BF16, L>(a, acc, tsc, o0 + wo * WO, t0 + wt * WT, ylds);
+        if (a.odt == TLQ_F16) store_rows_lds<F16, L>(a, Yo, acc, tsc, o0 + wo * WO, t0 + wt * WT, ylds);
+        else store_rows_lds<BF16, L>(a, Yo, acc, tsc, o0 + wo * WO, t0 + wt * WT, ylds);
         return;
       }
     }
@@ -333,10 +336,10 @@ __device__ __forceinline__ void tile_epilogue(const GemmDev& a, const Acc& acc, 
         const int64_t o = o0 + wo * WO + L::row(q, lane);
         float y[4] = {sg * L::get(acc, q, tb, 0), sg * L::get(acc, q, tb, 1), sg * L::get(acc, q, tb, 2),
                       sg * L::get(acc, q, tb, 3)};
-        if (o + 3 < a.c_out) store_y4(a.Yout, a.odt, t * a.ldo + o, y);
+        if (o + 3 < a.c_out) store_y4(Yo, a.odt, t * a.ldo + o, y);
         else
           for (int r = 0; r < 4; ++r)
-            if (o + r < a.c_out) store_y1(a.Yout, a.odt, t * a.ldo + o + r, y[r]);
+            if (o + r < a.c_out) store_y1(Yo, a.odt, t * a.ldo + o + r, y[r]);
       }
     }
     return;
@@ -406,25 +409,33 @@ __device__ __forceinline__ void tile_epilogue(const GemmDev& a, const Acc& acc, 
 __host__ __device__ __forceinline__ bool decode_tile(const GemmDev& a, int64_t bid, int& cand, int& to, int& tt) {
   const int64_t round = bid / (8 * PATCH_O * PATCH_T);
   const int within = (int)(bid % (8 * PATCH_O * PATCH_T));
-  const int64_t patch = round * 8 + (within & 7);
+  int64_t patch = round * 8 + (within & 7);
   const int slot = within >> 3;
   if (patch >= a.n_patches) return false;
+  // candidate-outermost order: the same walk with one candidate, repeated per candidate
+  int n_cand = a.n_cand, cand0 = 0;
+  if (a.cand_outer) {
+    const int64_t per = a.n_patches / a.n_cand;
+    cand0 = (int)(patch / per);
+    patch %= per;
+    n_cand = 1;
+  }
   const int n_full = a.rag ? a.npo - 1 : a.npo;
   const int ragp_full = a.rag ? (a.cpt * PATCH_T + a.rag_pt - 1) / a.rag_pt : 0;
-  const int64_t chunk_sz = (int64_t)a.n_cand * (n_full * a.cpt + ragp_full);
+  const int64_t chunk_sz = (int64_t)n_cand * (n_full * a.cpt + ragp_full);
   const int chunk = (int)(patch / chunk_sz);
   const int crem = (int)(patch % chunk_sz);
   const int cw = (a.npt - chunk * a.cpt) < a.cpt ? (a.npt - chunk * a.cpt) : a.cpt;
-  const int nfull_p = n_full * a.n_cand * cw;
+  const int nfull_p = n_full * n_cand * cw;
   if (crem < nfull_p) {
-    const int r2 = crem % (a.n_cand * cw);
-    cand = r2 / cw;
-    to = (crem / (a.n_cand * cw)) * PATCH_O + (slot % PATCH_O);
+    const int r2 = crem % (n_cand * cw);
+    cand = cand0 + r2 / cw;
+    to = (crem / (n_cand * cw)) * PATCH_O + (slot % PATCH_O);
     tt = (chunk * a.cpt + r2 % cw) * PATCH_T + (slot / PATCH_O);
   } else {
     const int ragp = (cw * PATCH_T + a.rag_pt - 1) / a.rag_pt;
     const int r2 = crem - nfull_p, col = slot / a.rag;
-    cand = r2 / ragp;
+    cand = cand0 + r2 / ragp;
     if (col >= a.rag_pt) return false;
     to = n_full * PATCH_O + (slot % a.rag);
     tt = chunk * a.cpt * PATCH_T + (r2 % ragp) * a.rag_pt + col;
@@ -796,6 +807,7 @@ static GemmDev make_dev(const GemmArgs& g) {
   d.w_cand_stride = g.w_cand_stride; d.n_cand = g.n_cand;
   d.Yref = g.Yref; d.ldy = g.ldy; d.ydt = g.yref_dtype; d.token_w = g.token_w;
   d.y_cand_stride = g.y_cand_stride; d.tri = g.tri ? 1 : 0;
+  d.cand_outer = g.cand_outer ? 1 : 0; d.o_cand_stride = g.o_cand_stride;
   d.partial = g.partial; d.tok_partial = g.tok_partial;
   d.Yout = g.Yout; d.ldo = g.ldo; d.odt = g.yout_dtype;
   int64_t to, tt;
@@ -853,30 +865,33 @@ static hipError_t launch_gemm(const GemmArgs& g, const char* name, hipStream_t s
   return hipGetLastError();
 }
 
-// Host-side check of the block -> tile map for one problem shape: walks every block id of the
-// launch and counts how often each (candidate, tile) is produced.  Returns the number of tiles
-// that are not produced exactly once (0 = the map is a bijection onto the tiles), or -1 for an
-// invalid shape.  *blocks_out receives the grid size.
+// Host-side check of the block -> tile map for one problem shape, in both block orders (candidates
+// inside every patch row, and candidate-outermost): walks every block id of the launch and counts
+// how often each (candidate, tile) is produced.  Returns the number of tiles that are not produced
+// exactly once (0 = both maps are bijections onto the tiles), or -1 for an invalid shape.
+// *blocks_out receives the grid size.
 int64_t tile_map_defects(int64_t n_tok, int64_t c_in, int64_t c_out, int n_cand, int64_t* blocks_out) {
   if (n_tok <= 0 || c_in <= 0 || c_out <= 0 || n_cand <= 0) return -1;
-  GemmArgs g{};
-  g.n_tok = n_tok; g.c_in = c_in; g.c_out = c_out; g.n_cand = n_cand;
-  const GemmDev d = make_dev(g);
-  const int64_t blocks = ceil_div(d.n_patches, 8) * 8 * PATCH_O * PATCH_T;
-  if (blocks_out) *blocks_out = blocks;
-  const int64_t tiles = (int64_t)n_cand * d.tiles_o * d.tiles_t;
-  unsigned char* seen = (unsigned char*)calloc((size_t)tiles, 1);
-  if (!seen) return -1;
   int64_t bad = 0;
-  for (int64_t b = 0; b < blocks; ++b) {
-    int cand, to, tt;
-    if (!decode_tile(d, b, cand, to, tt)) continue;
-    if (cand < 0 || cand >= n_cand || to < 0 || tt < 0) { ++bad; continue; }
-    unsigned char& c = seen[((int64_t)cand * d.tiles_o + to) * d.tiles_t + tt];
-    if (c < 255) ++c;
+  for (int order = 0; order < 2; ++order) {
+    GemmArgs g{};
+    g.n_tok = n_tok; g.c_in = c_in; g.c_out = c_out; g.n_cand = n_cand; g.cand_outer = order != 0;
+    const GemmDev d = make_dev(g);
+    const int64_t blocks = ceil_div(d.n_patches, 8) * 8 * PATCH_O * PATCH_T;
+    if (blocks_out) *blocks_out = blocks;
+    const int64_t tiles = (int64_t)n_cand * d.tiles_o * d.tiles_t;
+    unsigned char* seen = (unsigned char*)calloc((size_t)tiles, 1);
+    if (!seen) return -1;
+    for (int64_t b = 0; b < blocks; ++b) {
+      int cand, to, tt;
+      if (!decode_tile(d, b, cand, to, tt)) continue;
+      if (cand < 0 || cand >= n_cand || to < 0 || tt < 0) { ++bad; continue; }
+      unsigned char& c = seen[((int64_t)cand * d.tiles_o + to) * d.tiles_t + tt];
+      if (c < 255) ++c;
+    }
+    for (int64_t i = 0; i < tiles; ++i) bad += seen[i] != 1;
+    free(seen);
   }
-  for (int64_t i = 0; i < tiles; ++i) bad += seen[i] != 1;
-  free(seen);
   return bad;
 }
 
@@ -885,7 +900,8 @@ hipError_t launch_gemm_loss(const GemmArgs& g, hipStream_t stream) {
   return launch_gemm<EPI_LOSS>(g, "gemm_loss", stream);
 }
 hipError_t launch_gemm_store(const GemmArgs& g, hipStream_t stream) {
-  if (g.tri && (g.n_tok != g.c_out || g.n_cand != 1)) return hipErrorInvalidValue;
+  if (g.tri && g.n_tok != g.c_out) return hipErrorInvalidValue;
+  if (g.n_cand != 1 && g.o_cand_stride == 0) return hipErrorInvalidValue;
   return launch_gemm<EPI_STORE>(g, g.tri ? "gemm_gram" : "gemm_store", stream);
 }
 hipError_t launch_gemm_dot(const GemmArgs& g, hipStream_t stream) {

@@ -115,6 +115,24 @@ __global__ __launch_bounds__(1024) void gram_diag_kernel(const float* __restrict
   }
 }
 
+// H[0] += H[1] + ... + H[n_split - 1] in that order, over the 64 x 64 blocks of the computed
+// triangle (split-k partial products, each [c_in, c_in] float, `stride` elements apart).
+__global__ __launch_bounds__(256) void gram_reduce_kernel(float* __restrict__ H, int64_t c_in, int n_split,
+                                                          int64_t stride) {
+  const int64_t a0 = (int64_t)blockIdx.y * GT, b0 = (int64_t)blockIdx.x * GT;
+  if ((b0 / 256) > (a0 / 256)) return;
+  for (int i = threadIdx.x; i < GT * GT / 4; i += 256) {
+    const int64_t a = a0 + i / (GT / 4), b = b0 + (i % (GT / 4)) * 4;
+    if (a >= c_in || b >= c_in) continue;     // c_in % 4 == 0: whole groups of four
+    float4 acc = *reinterpret_cast<const float4*>(H + a * c_in + b);
+    for (int k = 1; k < n_split; ++k) {
+      const float4 v = *reinterpret_cast<const float4*>(H + k * stride + a * c_in + b);
+      acc.x += v.x; acc.y += v.y; acc.z += v.z; acc.w += v.w;
+    }
+    *reinterpret_cast<float4*>(H + a * c_in + b) = acc;
+  }
+}
+
 // C[a,b] = fp16(H[a,b] * 2^-(e_a + e_b)).  H holds the 256 x 256 tiles whose column tile is not
 // beyond their row tile; the others are read from the mirrored position.  A 64 x 64 block lies
 // inside one such tile, so the choice is uniform per block.
@@ -159,11 +177,13 @@ hipError_t launch_gram_operand(const void* X, int64_t n_tok, int64_t c_in, int64
   return hipGetLastError();
 }
 
-hipError_t launch_gram_finish(const float* H, int64_t c_in, const float* wmax, int* e, double* factor,
-                              float* col_scale, void* C, hipStream_t stream) {
+hipError_t launch_gram_finish(float* H, int64_t c_in, int n_split, int64_t split_stride, const float* wmax,
+                              int* e, double* factor, float* col_scale, void* C, hipStream_t stream) {
   const int64_t b = ceil_div(c_in, GT);
   if (b > 65535) return hipErrorInvalidValue;
-  ProfScope ps("gram_scale", stream, 6.0 * (double)c_in * (double)c_in);
+  ProfScope ps("gram_scale", stream, (6.0 + 2.0 * n_split) * (double)c_in * (double)c_in);
+  if (n_split > 1)
+    gram_reduce_kernel<<<dim3((unsigned)b, (unsigned)b), 256, 0, stream>>>(H, c_in, n_split, split_stride);
   gram_diag_kernel<<<1, 1024, 0, stream>>>(H, c_in, wmax, e, col_scale, factor);
   gram_convert_kernel<<<dim3((unsigned)b, (unsigned)b), 256, 0, stream>>>(H, c_in, e, (uint16_t*)C);
   return hipGetLastError();

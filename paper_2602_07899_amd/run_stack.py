@@ -23,7 +23,7 @@ from . import tlq
 from . import workloads as wl
 
 SEARCH_KERNELS = ("xstat_partial", "xstat_final", "scale_table", "fake_quant", "gemm_loss", "finalize", "bf16_to_f16",
-                  "act_quant")
+                  "act_quant", "gram_operand", "gemm_gram", "gram_scale", "gemm_gram_loss")
 BLOCK_KERNELS = ("rmsnorm_mul", "causal_attention", "silu_mul", "residual_add")
 SELECT_KERNELS = ("token_importance", "topk_mask")
 
@@ -83,7 +83,7 @@ def topk_xstat_fn(sw, n_samples, p, dev, dtype, frac=0.5):
 
 
 def run(stack_name, bits, mode="passact2", joint=False, n_layers=None, n_samples=None, journal_path=None,
-        act_bits=0, log=print, group=None, symmetric=False, xstat="mean"):
+        act_bits=0, log=print, group=None, symmetric=False, xstat="mean", strategy="tokens"):
     import torch
     if not torch.cuda.is_available():
         raise RuntimeError("run_stack needs a GPU")
@@ -99,7 +99,8 @@ def run(stack_name, bits, mode="passact2", joint=False, n_layers=None, n_samples
     al = torch.from_numpy(wl.alpha_grid(sw.n_alpha)).to(dev)
     jcfg = {"stack": stack_name, "seed": sw.seed, "bits": bits, "group": p.group, "symmetric": int(p.symmetric),
             "act_bits": act_bits, "mode": mode, "joint": bool(joint), "x_stat": xstat, "xstat_kind": int(p.xstat_kind),
-            "n_samples": int(n_samples or sw.n_samples), "n_alpha": sw.n_alpha, "dtype": sw.act_dtype}
+            "n_samples": int(n_samples or sw.n_samples), "n_alpha": sw.n_alpha, "dtype": sw.act_dtype,
+            "strategy": strategy}
     journal = gstack.Journal(journal_path, config=jcfg) if journal_path else None
     tlq.profile_reset()
     tlq.profile_enable(True)
@@ -117,7 +118,8 @@ def run(stack_name, bits, mode="passact2", joint=False, n_layers=None, n_samples
 
     xfn = topk_xstat_fn(sw, n_samples or sw.n_samples, p, dev, dtype) if xstat == "topk" else None
     _, hq, hf = gstack.run_stack(h0, device_weights(sw, dev, dtype), layers, w, al, p, sw.n_heads, sw.seq_len,
-                                 mode=mode, joint=joint, journal=journal, on_layer=on_layer, xstat_fn=xfn)
+                                 mode=mode, joint=joint, journal=journal, on_layer=on_layer, xstat_fn=xfn,
+                                 strategy=strategy)
     torch.cuda.synchronize()
     wall = time.time() - t0
     tlq.profile_enable(False)
@@ -126,10 +128,10 @@ def run(stack_name, bits, mode="passact2", joint=False, n_layers=None, n_samples
     block_ms = sum(k.total_ms for n, k in prof.items() if n in BLOCK_KERNELS)
     prop_ms = sum(k.total_ms for n, k in prof.items()
                   if n not in SEARCH_KERNELS and n not in BLOCK_KERNELS and n not in SELECT_KERNELS)
-    gl = prof.get("gemm_loss")
+    gl = prof.get("gemm_gram_loss" if strategy == "gram" else "gemm_loss")
     out = {
         "stack": stack_name, "bits": bits, "group": p.group, "symmetric": bool(p.symmetric), "mode": mode,
-        "joint": joint, "act_bits": act_bits, "x_stat": xstat, "layers": layers,
+        "joint": joint, "act_bits": act_bits, "x_stat": xstat, "strategy": strategy, "layers": layers,
         "n_tok": int(h0.shape[0]), "hidden": sw.hidden, "ffn": sw.ffn, "dtype": sw.act_dtype,
         # search = S0..S5; propagate = full-precision targets and the quantised outputs fed forward (S6);
         # block = the decoder block between the linears; the rest is weight generation and host time
@@ -161,11 +163,14 @@ def main():
     ap.add_argument("--symmetric", action="store_true")
     ap.add_argument("--xstat", default="mean", choices=("mean", "topk"),
                     help="mean |x| (default) or the maximum over the Top-50%% positions by synthetic gradient norm")
+    ap.add_argument("--strategy", default="tokens", choices=("tokens", "gram"),
+                    help="tokens: every candidate contracts the tokens; gram: candidates are evaluated through the "
+                         "weighted second-moment matrix of the exposed input (weight-only, not passact1)")
     ap.add_argument("--journal", default=None)
     ap.add_argument("--brief", action="store_true", help="leave the per-block records out of the summary")
     a = ap.parse_args()
     out = run(a.stack, a.bits, a.mode, a.joint, a.layers, a.samples, a.journal, a.act_bits, group=a.group,
-              symmetric=a.symmetric, xstat=a.xstat)
+              symmetric=a.symmetric, xstat=a.xstat, strategy=a.strategy)
     if a.brief:
         out.pop("blocks")
     print(json.dumps(out))

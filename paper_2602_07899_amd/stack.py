@@ -87,7 +87,7 @@ class Journal:
 
 
 def run_stack(h0, weights_fn, n_layers, token_w, alpha_grid, p, n_heads, seq_len, mode="passact2",
-              joint=False, journal=None, keep=False, on_layer=None, xstat_fn=None):
+              joint=False, journal=None, keep=False, on_layer=None, xstat_fn=None, strategy="tokens"):
     """h0 [n_tok, n_heads*128] device tensor in the activation type; weights_fn(layer)
     returns the 7 device weight matrices of one block (LINEARS order).  Returns
     (records, h_q, h_fp): records[layer][linear] holds device tensors best_idx, losses,
@@ -96,9 +96,15 @@ def run_stack(h0, weights_fn, n_layers, token_w, alpha_grid, p, n_heads, seq_len
     mode == "passact1").  xstat_fn(layer, names, X) may return a device float vector with the
     per-channel statistic of a group's exposed input (e.g. the gradient-guided Top-K maximum,
     Sec. 3.1.2, built with tlq.token_importance / topk_mask / x_stat_masked); None = the
-    statistic p.xstat_kind names."""
+    statistic p.xstat_kind names.  strategy "gram" evaluates the candidates through the weighted
+    second-moment matrix of each group's exposed input (tlq.token_gram / scale_search_gram): weight-only
+    settings whose target is f_fp of that same input, i.e. not PassAct1; the target then is the exact
+    product and, under PassAct2, the full-precision outputs are not formed at all."""
     import torch
     assert mode in ("none", "passact1", "passact2")
+    assert strategy in ("tokens", "gram")
+    gram = strategy == "gram"
+    assert not gram or (mode != "passact1" and p.act_bits == 0), "the second-moment form needs f_q linear in the searched input"
     dev, act = h0.device, h0.dtype
     n_tok, d = h0.shape
     assert d == n_heads * 128 and n_tok % seq_len == 0
@@ -110,7 +116,9 @@ def run_stack(h0, weights_fn, n_layers, token_w, alpha_grid, p, n_heads, seq_len
     ws_cache = {}
 
     def workspace(c_in, c_out):
-        need = max(tlq.scale_search_workspace_bytes(n_tok, c_in, c_out, na, p),
+        need = max(tlq.scale_search_gram_workspace_bytes(c_in, c_out, na, p) if gram else
+                   tlq.scale_search_workspace_bytes(n_tok, c_in, c_out, na, p),
+                   tlq.token_gram_workspace_bytes(n_tok, c_in) if gram else 0,
                    tlq.apply_best_workspace_bytes(n_tok, c_in, c_out, p), tlq.x_stat_workspace_bytes(n_tok, c_in))
         if ws_cache.get("n", 0) < need:
             ws_cache["t"] = None
@@ -130,11 +138,13 @@ def run_stack(h0, weights_fn, n_layers, token_w, alpha_grid, p, n_heads, seq_len
         (column slices of one matrix each)."""
         widths = [W.shape[0] for W in Ws]
         c_in, tot = Ws[0].shape[1], sum(widths)
-        Y = new(tot, y_dt)
         offs = [sum(widths[:i]) for i in range(len(Ws))]
-        Ys = [Y[:, o:o + w] for o, w in zip(offs, widths)]
+        need_y = not (gram and mode == "passact2")       # the target enters only through the matrix there
+        Y = new(tot, y_dt) if need_y else None
+        Ys = [Y[:, o:o + w] for o, w in zip(offs, widths)] if need_y else [None] * len(Ws)
         for W, Yi in zip(Ws, Ys):
-            tlq.ref_output(Xfp, W, Yi, p)
+            if need_y:
+                tlq.ref_output(Xfp, W, Yi, p)
         Z = None if mode == "none" else new(tot)
         # once per distinct exposed input: the channel statistic and (bf16) the fp16 re-expression
         xs_in = xstat_fn(layer, names, Xq) if xstat_fn is not None else None
@@ -146,6 +156,14 @@ def run_stack(h0, weights_fn, n_layers, token_w, alpha_grid, p, n_heads, seq_len
         if pb:
             prep = prepared_buffer(pb)
             tlq.prepare_tokens(Xq, p, prep)
+        gm = None
+        if gram:      # once per distinct exposed input as well
+            gb = tlq.token_gram_bytes(c_in)
+            if ws_cache.get("gn", 0) < gb:
+                ws_cache["g"] = None
+                ws_cache["g"] = torch.empty(gb, dtype=torch.uint8, device=dev)
+                ws_cache["gn"] = gb
+            gm = tlq.token_gram(Xq, token_w, p, ws_cache["g"][:gb], workspace=workspace(c_in, max(widths)))
         units = [(names, torch.cat(Ws, dim=0) if len(Ws) > 1 else Ws[0], Y, Z)] if joint else \
                 [((n,), W, Yi, None if Z is None else Z[:, o:o + w]) for n, W, Yi, o, w in zip(names, Ws, Ys, offs, widths)]
         for unames, W, Yu, Zu in units:
@@ -162,8 +180,11 @@ def run_stack(h0, weights_fn, n_layers, token_w, alpha_grid, p, n_heads, seq_len
                 idx.fill_(old["best_idx"])
                 losses.copy_(torch.tensor(old["losses"], dtype=torch.float32))
             else:
-                tlq.scale_search(Xq, W, Yu, token_w, alpha_grid, p, best, idx, losses, x_stat_in=xs_in,
-                                 workspace=ws, prepared=prep)
+                if gram:
+                    tlq.scale_search_gram(gm, W, alpha_grid, p, xs_in, best, idx, losses, workspace=ws)
+                else:
+                    tlq.scale_search(Xq, W, Yu, token_w, alpha_grid, p, best, idx, losses, x_stat_in=xs_in,
+                                     workspace=ws, prepared=prep)
                 if journal is not None:
                     li, ll = int(idx.item()), [float(v) for v in losses.tolist()]
                     for n in unames:

@@ -198,6 +198,63 @@ def test_stack_free_running(gpu, mode, joint):
         assert bool((hn == hf).all())
 
 
+@pytest.mark.parametrize("mode,joint", [("passact2", False), ("passact2", True), ("none", False)])
+def test_stack_gram_strategy(gpu, mode, joint):
+    """The second-moment strategy of the stack driver.  Teacher-forced: every search unit of the
+    oracle's run is repeated through tlq.token_gram / scale_search_gram on the ORACLE's exposed
+    input and compared with the oracle's search against the exact full-precision target of that
+    input.  Free-running: the driver with strategy="gram" against the oracle's run (whose targets
+    are rounded to bf16, hence the looser bound) and against the token strategy's choices."""
+    import torch
+    sw, h0, Ws, w, al, tW = _mini(gpu)
+    bits = 4
+    recs = ost.run_stack(h0, Ws, w, bits, sw.group, al, sw.n_heads, sw.seq_len, BF, mode=mode, joint=joint)
+    p = tlq.params(bits=bits, group=sw.group, x_dtype=tlq.BF16, yref_dtype=tlq.BF16)
+    tw, tal = torch.from_numpy(w).to(gpu), torch.from_numpy(al).to(gpu)
+    for l, layer in enumerate(recs):
+        for names in gstack.GROUPS:
+            X = layer[names[0]]["X"]
+            ci = X.shape[1]
+            Xd = dev(X, gpu, True)
+            xs = torch.empty(ci, dtype=torch.float32, device=gpu)
+            tlq.x_stat(Xd, p, xs)
+            gram = torch.empty(tlq.token_gram_bytes(ci), dtype=torch.uint8, device=gpu)
+            tlq.token_gram(Xd, tw, p, gram)
+            for un in ([names] if joint else [(n,) for n in names]):
+                W = np.concatenate([Ws[l][ost.LINEARS.index(n)] for n in un], axis=0)
+                best = torch.empty(ci, dtype=torch.float32, device=gpu)
+                idx = torch.empty(1, dtype=torch.int32, device=gpu)
+                losses = torch.empty(al.size, dtype=torch.float32, device=gpu)
+                tlq.scale_search_gram(gram, dev(W, gpu, True), tal, p, xs, best, idx, losses)
+                ref = orc.scale_search(X, W, orc.ref_output(X, W), w, bits, sw.group, al)
+                gl, ol = losses.cpu().numpy().astype(np.float64), ref["losses"]
+                rel = np.abs(gl - ol) / ol
+                assert rel.max() < 1e-3, (l, un, rel.max())
+                if int(idx.item()) != ref["best_idx"]:
+                    srt = np.sort(ol)
+                    assert (srt[1] - srt[0]) / srt[0] < 1e-3, (l, un)
+    pg = tlq.params(bits=bits, group=sw.group, x_dtype=tlq.BF16, yref_dtype=tlq.BF16)
+    run = lambda strategy: gstack.run_stack(dev(h0, gpu, True), lambda l: tW[l], sw.n_layers, tw, tal, pg, sw.n_heads,
+                                            sw.seq_len, mode=mode, joint=joint, keep=True, strategy=strategy)
+    out, hq, hf = run("gram")
+    outt, hqt, _ = run("tokens")
+    for l, (g, t, o) in enumerate(zip(out, outt, recs)):
+        for n in ost.LINEARS:
+            gl = g[n]["losses"].cpu().numpy().astype(np.float64)
+            ol = np.asarray(o[n]["res"]["losses"], np.float64)
+            assert np.abs(gl - ol).max() / ol.max() < 2e-2, (l, n)
+            tl = t[n]["losses"].cpu().numpy().astype(np.float64)
+            if int(g[n]["best_idx"].item()) != int(t[n]["best_idx"].item()):
+                srt = np.sort(tl)
+                assert (srt[1] - srt[0]) / srt[0] < 2e-2, (l, n)
+    ho = np.asarray(recs[-1]["h_out"], np.float64)
+    assert np.linalg.norm(host(hq) - ho) <= 2e-2 * np.linalg.norm(ho)
+    assert np.linalg.norm(host(hq) - host(hqt)) <= 2e-2 * np.linalg.norm(ho)
+    with pytest.raises(AssertionError):
+        gstack.run_stack(dev(h0, gpu, True), lambda l: tW[l], 1, tw, tal, pg, sw.n_heads, sw.seq_len, mode="passact1",
+                         strategy="gram")
+
+
 def test_stack_journal_resume(gpu, tmp_path):
     import torch
     sw, h0, Ws, w, al, tW = _mini(gpu)
