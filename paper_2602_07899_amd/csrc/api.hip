@@ -154,7 +154,7 @@ GramPlan plan_gram(void* ws, int64_t n_tok, int64_t c_in) {
   int64_t to, tt;
   gemm_tile_counts(c_in, c_in, &to, &tt);
   const int64_t live = to * (to + 1) / 2;
-  int64_t ns = (2048 + live - 1) / live;
+  int64_t ns = (6000 + live - 1) / live;               // measured: more, shorter splits run faster
   const int64_t max_ns = n_tok / 4096;                 // at least 4096 tokens (64 k-tiles) per split
   ns = ns > 16 ? 16 : ns;
   ns = ns > max_ns ? max_ns : ns;
@@ -540,7 +540,7 @@ tlq_status tlq_token_gram(const void* X, int64_t n_tok, int64_t c_in, int64_t ld
   r.X = g.xst; r.n_tok = c_in; r.c_in = g.kc; r.ldx = g.kp; r.x_cand_stride = g.kc;
   r.Wh = g.xst; r.c_out = c_in; r.ldw = g.kp; r.w_cand_stride = g.kc; r.n_cand = g.n_split; r.bf16 = false;
   r.Yout = g.H; r.ldo = c_in; r.yout_dtype = TLQ_F32; r.o_cand_stride = c_in * c_in; r.tri = true;
-  r.cand_outer = true;
+  r.cand_outer = true; r.wide_patch = c_in >= 32 * 256;   // measured: 8 x 4 patches pay from ~32 tile rows on
   TLQ_HIP(launch_gemm_store(r, st));
   return hip_status(launch_gram_finish(g.H, c_in, g.n_split, c_in * c_in, g.wmax, g.e, v.factor, v.col_scale,
                                        v.C, st));
@@ -587,9 +587,11 @@ tlq_status tlq_scale_search_gram(const void* gram, int64_t c_in, const void* W, 
   g.Wh = v.C; g.c_out = c_in; g.ldw = c_in; g.w_cand_stride = 0; g.n_cand = n_alpha; g.bf16 = false;
   g.Yref = s.dq; g.ldy = c_in; g.yref_dtype = TLQ_F16; g.y_cand_stride = c_out * c_in;
   g.partial = s.partial; g.cand_outer = true;   // D'_k and C stay cache-resident for one candidate at a time
+  g.wide_patch = true;   // consecutive patches keep their 8 panels of C and fetch 4 new ones of D'_k
+  g.sym_k = true;        // C is symmetric: contract from each tile's diagonal block on, double afterwards
   TLQ_HIP(launch_gemm_dot(g, st));
   TLQ_HIP(launch_finalize(s.partial, n_alpha, s.tiles_o * s.tiles_t, c_out, s.s_table, c_in, losses,
-                          best_idx, best_scales, st, v.factor));
+                          best_idx, best_scales, st, v.factor, gemm_dot_symmetric(g) ? 2.0 : 1.0));
   return TLQ_OK;
 }
 

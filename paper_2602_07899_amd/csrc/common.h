@@ -124,6 +124,8 @@ struct GemmArgs {
   int64_t y_cand_stride;   // launch_gemm_dot: elements between per-candidate Y matrices
   bool tri;                // launch_gemm_store of a symmetric product (X == Wh): tiles with tile row <= tile column only
   bool cand_outer;         // walk the candidates one after the other instead of inside every patch row
+  bool wide_patch;         // L2 patches of 8 x 4 tiles (output rows x tokens) instead of 4 x 8
+  bool sym_k;              // launch_gemm_dot: Wh is symmetric [c_in, c_in] and Y == X (a quadratic form)
   int64_t o_cand_stride;   // launch_gemm_store with n_cand > 1: elements between per-candidate outputs
   float* partial;          // [n_cand, tiles_o, tiles_t] float
   float* tok_partial;      // [tiles_o, n_tok] float or NULL (single candidate only)
@@ -136,6 +138,8 @@ hipError_t launch_gemm_loss(const GemmArgs& a, hipStream_t stream);
 hipError_t launch_gemm_store(const GemmArgs& a, hipStream_t stream);
 // partial[k, tile] = sum over the tile of (X_k Wh^T)[t,o] * Y_k[t,o]  (no token weights)
 hipError_t launch_gemm_dot(const GemmArgs& a, hipStream_t stream);
+// true when that launch uses the symmetry (sym_k) and returns HALF of every partial sum
+bool gemm_dot_symmetric(const GemmArgs& a);
 
 // Second-moment form (gram.hip).  out[c, t] = fp16(X[t,c] * sqrt(w_t / max w)) as [c_in, kp] with zero
 // columns for n_tok <= t < kp; *wmax receives max_t w_t.
@@ -156,7 +160,8 @@ hipError_t launch_sub_from_y(const void* Y, int64_t ldy, int ydt, float* D, int6
 // `factor` (optional): device double multiplied into every loss
 hipError_t launch_finalize(const float* partial, int n_cand, int64_t tiles_per_cand, int64_t c_out,
                            const float* s_table, int64_t c_in, float* losses, int32_t* best_idx,
-                           float* best_scales, hipStream_t stream, const double* factor = nullptr);
+                           float* best_scales, hipStream_t stream, const double* factor = nullptr,
+                           double host_factor = 1.0);
 hipError_t launch_token_err_reduce(const float* tok_partial, int64_t tiles_o, int64_t n_tok,
                                    int64_t c_out, float* per_token_err, hipStream_t stream);
 

@@ -99,7 +99,10 @@ template <int IA, int JB> struct Acc16 {   // acc[IA][JB] of f32x4 (16x16x32)
 enum { EPI_LOSS = 0, EPI_LOSS_TOK = 1, EPI_STORE = 2, EPI_DOT = 3 };
 constexpr int BK = 64;        // halves per k-tile
 constexpr int ROWB = BK * 2;  // bytes per LDS row
-constexpr int PATCH_O = 4, PATCH_T = 8;  // tiles per L2 patch (one patch per XCD at a time)
+// An L2 patch (one per XCD at a time) is po x pt tiles = 32 workgroups: 4 x 8 by default (4 operand
+// panels that stay while the walk moves along the tokens + 8 token panels), or 8 x 4 for launches
+// whose walk keeps the output-side panels and changes the token-side ones from patch to patch.
+constexpr int PATCH_SLOTS = 32, kXcd = 8;
 
 struct GemmDev {
   const uint16_t* X; int64_t n_tok, c_in, ldx, x_cand_stride;
@@ -116,6 +119,7 @@ struct GemmDev {
   int64_t n_patches;
   int cpt;          // token patches per chunk (see make_dev)
   int rag, rag_pt;  // tile rows of the last, incomplete patch row (0 = none) and its patch width in tiles
+  int po, pt;       // patch shape in tiles (po * pt == PATCH_SLOTS)
 };
 
 __device__ __forceinline__ int swz(int row, int chunk) { return chunk ^ ((row >> 1) & 7); }
@@ -398,19 +402,20 @@ __device__ __forceinline__ void tile_epilogue(const GemmDev& a, const Acc& acc, 
 }
 
 // Block id -> (candidate, tile row, tile column).  Blocks are dealt to the 8 XCDs round-robin by
-// block id, so block id = (round, xcd, slot) and every XCD works on one patch of PATCH_O x PATCH_T
-// tiles at a time (32 CUs = 32 tiles sharing 4 weight panels and 8 token panels in its L2).
+// block id, so block id = (round, xcd, slot) and every XCD works on one patch of po x pt tiles at a
+// time (32 CUs = 32 tiles sharing, by default, 4 weight panels and 8 token panels in its L2).
 // Patch order: chunks of cpt token patches; inside a chunk, for every output patch row, every
 // candidate visits the chunk's token patches.  The chunk's tokens and the row's slice of Y_ref are
 // thus shared by all candidates while they are hot in the last-level cache, and each candidate's
-// weights are streamed once per chunk.  When tiles_o is not a multiple of PATCH_O the last patch row
+// weights are streamed once per chunk.  When tiles_o is not a multiple of po the last patch row
 // has `rag` tile rows and uses patches of rag x rag_pt tiles, so that (nearly) every slot of a patch
 // is a live tile.  Returns false for a slot that has no tile.
 __host__ __device__ __forceinline__ bool decode_tile(const GemmDev& a, int64_t bid, int& cand, int& to, int& tt) {
-  const int64_t round = bid / (8 * PATCH_O * PATCH_T);
-  const int within = (int)(bid % (8 * PATCH_O * PATCH_T));
-  int64_t patch = round * 8 + (within & 7);
-  const int slot = within >> 3;
+  const int PATCH_O = a.po, PATCH_T = a.pt;
+  const int64_t round = bid / (kXcd * PATCH_SLOTS);
+  const int within = (int)(bid % (kXcd * PATCH_SLOTS));
+  int64_t patch = round * kXcd + (within & (kXcd - 1));
+  const int slot = within / kXcd;
   if (patch >= a.n_patches) return false;
   // candidate-outermost order: the same walk with one candidate, repeated per candidate
   int n_cand = a.n_cand, cand0 = 0;
@@ -619,7 +624,11 @@ __device__ __forceinline__ void wait_vmcnt() {
 // The side operations are slotted two at a time behind the first MFMAs of a phase (measured best:
 // one per MFMA over the whole phase -3 %, four at a time -2 %), so that neither the LDS queue nor
 // the texture-address queue sees a burst that would hold back the in-order MFMA issue.
-template <typename T, int NSTAGE, int EPI>
+// SYMK: Wh is a symmetric square matrix (c_out == c_in) and the epilogue forms a quadratic form in
+// it (EPI_DOT with Y == X): the tile with first output row o0 contracts only k >= o0, and its
+// first four k-tiles - the diagonal block - count half.  The caller doubles the result:
+// 2 * (sum_{k > block} + 1/2 sum_{k in block}) = the full contraction, at about half the flops.
+template <typename T, int NSTAGE, int EPI, bool SYMK = false>
 __global__ __launch_bounds__(512) void gemm_dma_kernel(GemmDev a) {
 #if defined(__HIP_DEVICE_COMPILE__)  // the body uses gfx950 builtins the host pass cannot parse
   constexpr int BK_ = 64, BO = 256, BT = 256, NWO = 2, NWT = 4, NW = NWO * NWT, WO = BO / NWO, WT = BT / NWT;
@@ -647,12 +656,14 @@ __global__ __launch_bounds__(512) void gemm_dma_kernel(GemmDev a) {
   // buffer descriptors over the valid rows of this block's two operand panels
   const int64_t vro = (a.c_out - o0) < BO ? (a.c_out - o0) : BO;
   const int64_t vrt = (a.n_tok - t0) < BT ? (a.n_tok - t0) : BT;
-  const uint16_t* pA = a.Wh + (int64_t)cand * a.w_cand_stride + o0 * a.ldw;
-  const uint16_t* pB = a.X + (int64_t)cand * a.x_cand_stride + t0 * a.ldx;
+  const int64_t kskip = SYMK ? o0 : 0;    // first contraction index (a multiple of the tile height)
+  const int64_t klen = a.c_in - kskip;
+  const uint16_t* pA = a.Wh + (int64_t)cand * a.w_cand_stride + o0 * a.ldw + kskip;
+  const uint16_t* pB = a.X + (int64_t)cand * a.x_cand_stride + t0 * a.ldx + kskip;
   const __amdgpu_buffer_rsrc_t rA = __builtin_amdgcn_make_buffer_rsrc(
-      (void*)pA, 0, (int)(((vro - 1) * a.ldw + a.c_in) * 2), 0x00020000);
+      (void*)pA, 0, (int)(((vro - 1) * a.ldw + klen) * 2), 0x00020000);
   const __amdgpu_buffer_rsrc_t rB = __builtin_amdgcn_make_buffer_rsrc(
-      (void*)pB, 0, (int)(((vrt - 1) * a.ldx + a.c_in) * 2), 0x00020000);
+      (void*)pB, 0, (int)(((vrt - 1) * a.ldx + klen) * 2), 0x00020000);
 
   // per-lane global byte offsets of the chunks this lane fetches: LDS slot `p` of row r holds
   // chunk p ^ ((r / 2) % 8)
@@ -670,7 +681,7 @@ __global__ __launch_bounds__(512) void gemm_dma_kernel(GemmDev a) {
   // issued (the counter bookkeeping stays uniform) but with a per-lane offset
   // that is out of range for any descriptor, which touches no memory and
   // delivers zeros.
-  const int64_t nk = a.c_in / BK_;
+  const int64_t nk = klen / BK_;
   constexpr int kOutOfRange = (int)0x80000000u;
   auto dma1 = [&](auto dc, unsigned char* sbase, bool live, int so) {
     constexpr int d = decltype(dc)::value, j = d / 2;
@@ -761,7 +772,15 @@ __global__ __launch_bounds__(512) void gemm_dma_kernel(GemmDev a) {
     lds_read128<m * 16 * RB>(Fb[0][m], offB[0]);
   });
   lds_wait8(Fa[0][0], Fa[0][1], Fa[0][2], Fa[0][3], Fb[0][0], Fb[0][1], Fb[0][2], Fb[0][3]);
+  constexpr int64_t kDiagTiles = BO / BK_;   // k-tiles of the diagonal block (SYMK)
+  auto halve = [&]() {
+#pragma unroll
+    for (int i = 0; i < IA; ++i)
+#pragma unroll
+      for (int j = 0; j < JB; ++j) acc[i][j] *= 0.5f;
+  };
   for (int64_t kt = 0; kt < nk; ++kt) {
+    if (SYMK && kt == kDiagTiles) halve();
     const uint32_t so_cur = (uint32_t)((kt % NSTAGE) * STAGE);
     phase(I0{}, I0{}, I0{}, I1{}, I0{}, I0{}, offA[0] + so_cur, 0u, 0);
     lds_wait4(Fa[1][0], Fa[1][1], Fa[1][2], Fa[1][3]);
@@ -780,6 +799,7 @@ __global__ __launch_bounds__(512) void gemm_dma_kernel(GemmDev a) {
   }
   wait_vmcnt<0>();
   __syncthreads();
+  if (SYMK && nk <= kDiagTiles) halve();
 
   // every LDS-DMA write has landed and every wave is past its last fragment read:
   // the tile memory is free for the per-token row sums and the Y_ref / output staging
@@ -813,9 +833,11 @@ static GemmDev make_dev(const GemmArgs& g) {
   int64_t to, tt;
   gemm_tile_counts(g.n_tok, g.c_out, &to, &tt);
   d.tiles_o = (int)to; d.tiles_t = (int)tt;
+  d.po = g.wide_patch ? 8 : 4; d.pt = PATCH_SLOTS / d.po;
+  const int PATCH_O = d.po, PATCH_T = d.pt;
   d.npo = (int)ceil_div(to, PATCH_O); d.npt = (int)ceil_div(tt, PATCH_T);
   d.rag = (int)(to % PATCH_O);
-  d.rag_pt = d.rag == 0 ? PATCH_T : (d.rag == 3 ? 10 : (PATCH_O * PATCH_T) / d.rag);
+  d.rag_pt = d.rag == 0 ? PATCH_T : PATCH_SLOTS / d.rag;   // e.g. 3 rows -> patches of 3 x 10
   // Tokens of one chunk.  While all tokens fit in half of the 256 MB last-level cache there is one
   // chunk.  Otherwise a chunk holds the largest power-of-two number of token patches within that
   // budget: with 1, 2, 4 or 8 patches per (candidate, patch row) the round-robin deal keeps every XCD
@@ -827,7 +849,7 @@ static GemmDev make_dev(const GemmArgs& g) {
     d.cpt = d.npt;
   } else {
     d.cpt = 1;
-    while (d.cpt * 2 <= PATCH_T && (int64_t)d.cpt * 2 * patch_bytes <= kChunkBytes) d.cpt *= 2;
+    while (d.cpt * 2 <= kXcd && (int64_t)d.cpt * 2 * patch_bytes <= kChunkBytes) d.cpt *= 2;
   }
   {
     const int n_full = d.rag ? d.npo - 1 : d.npo;
@@ -841,19 +863,34 @@ static GemmDev make_dev(const GemmArgs& g) {
   return d;
 }
 
+// Whether launch_gemm_dot contracts only the upper part of a symmetric Wh (see SYMK): the caller
+// then has to double the partial sums.
+bool gemm_dot_symmetric(const GemmArgs& g) {
+  return g.sym_k && g.c_out == g.c_in && (g.c_in % kDmaBK) == 0 && g.ldw < (1 << 21) && g.ldx < (1 << 21);
+}
+
 template <int EPI>
 static hipError_t launch_gemm(const GemmArgs& g, const char* name, hipStream_t stream) {
   GemmDev d = make_dev(g);
   const int64_t rounds = ceil_div(d.n_patches, 8);
-  const int64_t blocks = rounds * 8 * PATCH_O * PATCH_T;
+  const int64_t blocks = rounds * kXcd * PATCH_SLOTS;
   if (blocks > 0x7fffffffLL) return hipErrorInvalidValue;
-  // (a symmetric product computes the tiles on and above the diagonal: about half)
-  const double tile_frac = g.tri ? 0.5 * (1.0 + 1.0 / (double)d.tiles_o) : 1.0;
-  ProfScope ps(name, stream, 2.0 * (double)g.n_tok * (double)g.c_in * (double)g.c_out * g.n_cand * tile_frac);
-  constexpr int NT = (kBO / kWO) * (kBT / kWT) * 64;
   // the pipelined kernel needs whole k-tiles and 32-bit byte offsets inside a 256-row panel
   const bool dma = (g.c_in % kDmaBK) == 0 && g.ldw < (1 << 21) && g.ldx < (1 << 21);
-  if (dma) {
+  const bool symk = EPI == EPI_DOT && dma && gemm_dot_symmetric(g);
+  // (a symmetric product computes the tiles on and above the diagonal, a symmetric contraction
+  // the k range from the diagonal block on: about half either way)
+  const double tile_frac = (g.tri || symk) ? 0.5 * (1.0 + 1.0 / (double)d.tiles_o) : 1.0;
+  ProfScope ps(name, stream, 2.0 * (double)g.n_tok * (double)g.c_in * (double)g.c_out * g.n_cand * tile_frac);
+  constexpr int NT = (kBO / kWO) * (kBT / kWT) * 64;
+  if (symk) {
+    if constexpr (EPI == EPI_DOT) {
+      if (!g.bf16)
+        gemm_dma_kernel<F16, kDmaStages, EPI_DOT, true><<<(unsigned)blocks, kDmaThreads, 0, stream>>>(d);
+      else
+        gemm_dma_kernel<BF16, kDmaStages, EPI_DOT, true><<<(unsigned)blocks, kDmaThreads, 0, stream>>>(d);
+    }
+  } else if (dma) {
     if (!g.bf16)
       gemm_dma_kernel<F16, kDmaStages, EPI><<<(unsigned)blocks, kDmaThreads, 0, stream>>>(d);
     else
@@ -866,19 +903,20 @@ static hipError_t launch_gemm(const GemmArgs& g, const char* name, hipStream_t s
 }
 
 // Host-side check of the block -> tile map for one problem shape, in both block orders (candidates
-// inside every patch row, and candidate-outermost): walks every block id of the launch and counts
+// inside every patch row, and candidate-outermost) and both patch shapes: walks every block id of the launch and counts
 // how often each (candidate, tile) is produced.  Returns the number of tiles that are not produced
 // exactly once (0 = both maps are bijections onto the tiles), or -1 for an invalid shape.
 // *blocks_out receives the grid size.
 int64_t tile_map_defects(int64_t n_tok, int64_t c_in, int64_t c_out, int n_cand, int64_t* blocks_out) {
   if (n_tok <= 0 || c_in <= 0 || c_out <= 0 || n_cand <= 0) return -1;
   int64_t bad = 0;
-  for (int order = 0; order < 2; ++order) {
+  for (int order = 0; order < 4; ++order) {
     GemmArgs g{};
-    g.n_tok = n_tok; g.c_in = c_in; g.c_out = c_out; g.n_cand = n_cand; g.cand_outer = order != 0;
+    g.n_tok = n_tok; g.c_in = c_in; g.c_out = c_out; g.n_cand = n_cand;
+    g.cand_outer = (order & 1) != 0; g.wide_patch = (order & 2) != 0;
     const GemmDev d = make_dev(g);
-    const int64_t blocks = ceil_div(d.n_patches, 8) * 8 * PATCH_O * PATCH_T;
-    if (blocks_out) *blocks_out = blocks;
+    const int64_t blocks = ceil_div(d.n_patches, kXcd) * kXcd * PATCH_SLOTS;
+    if (blocks_out && order == 0) *blocks_out = blocks;
     const int64_t tiles = (int64_t)n_cand * d.tiles_o * d.tiles_t;
     unsigned char* seen = (unsigned char*)calloc((size_t)tiles, 1);
     if (!seen) return -1;
