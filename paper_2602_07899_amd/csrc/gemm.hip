@@ -12,6 +12,12 @@
 // reduces to ONE float per (candidate, tile).  Candidate outputs never reach
 // HBM.
 //
+// The same kernels serve the second-moment form of the search (gram.hip): the product of the
+// transposed, weighted tokens with themselves (store epilogue, only the tiles of one triangle,
+// the long contraction split into "candidates" that are summed afterwards), and the quadratic
+// form of every candidate's weight error in that matrix (EPI_DOT: accumulator times Y instead of
+// the squared residual; SYMK: only the upper part of the symmetric operand is contracted).
+//
 // Two kernels share the tile epilogues and the block -> tile map:
 //   gemm_dma_kernel  the pipelined one (c_in % 64 == 0): 16x16x32 MFMA, operands brought
 //                    into LDS by LDS-DMA loads, two 64 KB stages, hand-placed waits;

@@ -14,6 +14,7 @@ sources still hash to the recorded fingerprint.
 from __future__ import annotations
 
 import collections
+import re
 import csv
 import glob
 import json
@@ -37,6 +38,10 @@ def _read(dirname, counter):
     return [(k, v) for _, k, v in rows]
 
 
+# the fused contraction + weighted-loss instantiation (epilogue 0) of the pipelined kernel
+_LOSS_KERNEL = re.compile(r"gemm_dma_kernel<tlq::\w+, \d+, 0[,>]")
+
+
 def main(prof_dir):
     sys.path.insert(0, ROOT)
     import bench
@@ -53,7 +58,7 @@ def main(prof_dir):
                     cur = {"cal": v, "gemm": []}
                     blocks.append(cur)
                 continue
-            if cur is not None and "gemm_dma_kernel" in k and ", 0>(" in k:
+            if cur is not None and _LOSS_KERNEL.search(k):
                 cur["gemm"].append(v)
         return blocks
 
