@@ -138,7 +138,40 @@ int main() {
   const size_t wsq = tlq_scale_search_workspace_bytes(256, 512, 512, 20, &q);
   EXPECT(tlq_scale_search_prepared(A, 256, 512, 512, A, 512, 512, A, 512, F, F, 20, &q, nullptr, F, I, F, nullptr, A, wsq, nullptr, ODD), TLQ_ERR_ALIGN);
 
-  // ---- f_fp, S6, glue
+  // ---- second-moment form
+  const size_t gb = tlq_token_gram_bytes(512);
+  EXPECT(gb >= (size_t)512 * 512 * 2 + 512 * 4 + 256, 1);
+  EXPECT(tlq_token_gram_bytes(0), 0);
+  const size_t gws = tlq_token_gram_workspace_bytes(9000, 512);
+  EXPECT(gws >= (size_t)9000 * 512 * 2 + (size_t)512 * 512 * 4, 1);
+  EXPECT(tlq_token_gram_workspace_bytes(0, 512), 0);
+  EXPECT(tlq_token_gram(nullptr, 9000, 512, 512, F, &p, A, gb, A, gws, nullptr), TLQ_ERR_NULL);
+  EXPECT(tlq_token_gram(A, 9000, 512, 512, nullptr, &p, A, gb, A, gws, nullptr), TLQ_ERR_NULL);
+  EXPECT(tlq_token_gram(A, 9000, 516, 520, F, &p, A, (size_t)1 << 30, A, (size_t)1 << 40, nullptr), TLQ_ERR_SHAPE);
+  EXPECT(tlq_token_gram(A, 9000, 512, 256, F, &p, A, gb, A, gws, nullptr), TLQ_ERR_SHAPE);
+  EXPECT(tlq_token_gram(ODD, 9000, 512, 512, F, &p, A, gb, A, gws, nullptr), TLQ_ERR_ALIGN);
+  EXPECT(tlq_token_gram(A, 9000, 512, 512, F, &p, A, gb - 1, A, gws, nullptr), TLQ_ERR_WORKSPACE);
+  EXPECT(tlq_token_gram(A, 9000, 512, 512, F, &p, nullptr, gb, A, gws, nullptr), TLQ_ERR_WORKSPACE);
+  EXPECT(tlq_token_gram(A, 9000, 512, 512, F, &p, ODD, gb, A, gws, nullptr), TLQ_ERR_ALIGN);
+  EXPECT(tlq_token_gram(A, 9000, 512, 512, F, &p, A, gb, A, gws - 1, nullptr), TLQ_ERR_WORKSPACE);
+  EXPECT(tlq_token_gram(A, 9000, 512, 512, F, &p, A, gb, ODD, gws, nullptr), TLQ_ERR_ALIGN);
+  const size_t gss = tlq_scale_search_gram_workspace_bytes(512, 384, 20, &p);
+  EXPECT(gss >= (size_t)20 * 384 * 512 * 2, 1);
+  EXPECT(tlq_scale_search_gram_workspace_bytes(512, 384, 0, &p), 0);
+  EXPECT(tlq_scale_search_gram_workspace_bytes(512, 384, 20, nullptr), 0);
+  EXPECT(tlq_scale_search_gram(nullptr, 512, A, 384, 512, F, 20, &p, F, F, I, F, nullptr, A, gss, nullptr), TLQ_ERR_NULL);
+  EXPECT(tlq_scale_search_gram(A, 512, A, 384, 512, F, 20, &p, nullptr, F, I, F, nullptr, A, gss, nullptr), TLQ_ERR_NULL);
+  q = p; q.act_bits = 8;
+  EXPECT(tlq_scale_search_gram(A, 512, A, 384, 512, F, 20, &q, F, F, I, F, nullptr, A, gss, nullptr), TLQ_ERR_UNSUPPORTED);
+  EXPECT(tlq_scale_search_gram(A, 512, A, 384, 512, F, 0, &p, F, F, I, F, nullptr, A, gss, nullptr), TLQ_ERR_SHAPE);
+  EXPECT(tlq_scale_search_gram(A, 520, A, 384, 520, F, 20, &p, F, F, I, F, nullptr, A, (size_t)1 << 40, nullptr), TLQ_ERR_SHAPE);
+  EXPECT(tlq_scale_search_gram(A, 512, A, 384, 256, F, 20, &p, F, F, I, F, nullptr, A, gss, nullptr), TLQ_ERR_SHAPE);
+  EXPECT(tlq_scale_search_gram(ODD, 512, A, 384, 512, F, 20, &p, F, F, I, F, nullptr, A, gss, nullptr), TLQ_ERR_ALIGN);
+  EXPECT(tlq_scale_search_gram(A, 512, ODD, 384, 512, F, 20, &p, F, F, I, F, nullptr, A, gss, nullptr), TLQ_ERR_ALIGN);
+  EXPECT(tlq_scale_search_gram(A, 512, A, 384, 512, F, 20, &p, F, F, I, F, nullptr, A, gss - 1, nullptr), TLQ_ERR_WORKSPACE);
+  EXPECT(tlq_scale_search_gram(A, 512, A, 384, 512, F, 20, &p, F, F, I, F, nullptr, ODD, gss, nullptr), TLQ_ERR_ALIGN);
+
+  // ---- f_fp, S6, glue  // ---- f_fp, S6, glue
   EXPECT(tlq_ref_output(A, 8, 128, 128, nullptr, 8, 128, A, 8, &p, nullptr), TLQ_ERR_NULL);
   EXPECT(tlq_ref_output(A, 8, 128, 128, A, 8, 128, A, 4, &p, nullptr), TLQ_ERR_SHAPE);
   EXPECT(tlq_ref_output(A, 8, 128, 128, A, 8, 128, ODD, 8, &p, nullptr), TLQ_ERR_ALIGN);
