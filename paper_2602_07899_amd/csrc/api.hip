@@ -588,10 +588,10 @@ tlq_status tlq_scale_search_gram(const void* gram, int64_t c_in, const void* W, 
   g.Yref = s.dq; g.ldy = c_in; g.yref_dtype = TLQ_F16; g.y_cand_stride = c_out * c_in;
   g.partial = s.partial; g.cand_outer = true;   // D'_k and C stay cache-resident for one candidate at a time
   g.wide_patch = true;   // consecutive patches keep their 8 panels of C and fetch 4 new ones of D'_k
-  g.sym_k = true;        // C is symmetric: contract from each tile's diagonal block on, double afterwards
+  g.sym_k = true;        // C is symmetric: contract from each tile's diagonal block on, the rest counted twice
   TLQ_HIP(launch_gemm_dot(g, st));
   TLQ_HIP(launch_finalize(s.partial, n_alpha, s.tiles_o * s.tiles_t, c_out, s.s_table, c_in, losses,
-                          best_idx, best_scales, st, v.factor, gemm_dot_symmetric(g) ? 2.0 : 1.0));
+                          best_idx, best_scales, st, v.factor));
   return TLQ_OK;
 }
 

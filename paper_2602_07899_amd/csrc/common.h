@@ -138,7 +138,7 @@ hipError_t launch_gemm_loss(const GemmArgs& a, hipStream_t stream);
 hipError_t launch_gemm_store(const GemmArgs& a, hipStream_t stream);
 // partial[k, tile] = sum over the tile of (X_k Wh^T)[t,o] * Y_k[t,o]  (no token weights)
 hipError_t launch_gemm_dot(const GemmArgs& a, hipStream_t stream);
-// true when that launch uses the symmetry (sym_k) and returns HALF of every partial sum
+// true when that launch uses the symmetry (sym_k: about half the flops, same partial sums)
 bool gemm_dot_symmetric(const GemmArgs& a);
 
 // Second-moment form (gram.hip).  out[c, t] = fp16(X[t,c] * sqrt(w_t / max w)) as [c_in, kp] with zero
@@ -160,8 +160,7 @@ hipError_t launch_sub_from_y(const void* Y, int64_t ldy, int ydt, float* D, int6
 // `factor` (optional): device double multiplied into every loss
 hipError_t launch_finalize(const float* partial, int n_cand, int64_t tiles_per_cand, int64_t c_out,
                            const float* s_table, int64_t c_in, float* losses, int32_t* best_idx,
-                           float* best_scales, hipStream_t stream, const double* factor = nullptr,
-                           double host_factor = 1.0);
+                           float* best_scales, hipStream_t stream, const double* factor = nullptr);
 hipError_t launch_token_err_reduce(const float* tok_partial, int64_t tiles_o, int64_t n_tok,
                                    int64_t c_out, float* per_token_err, hipStream_t stream);
 

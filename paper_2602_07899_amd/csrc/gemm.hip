@@ -631,9 +631,11 @@ __device__ __forceinline__ void wait_vmcnt() {
 // one per MFMA over the whole phase -3 %, four at a time -2 %), so that neither the LDS queue nor
 // the texture-address queue sees a burst that would hold back the in-order MFMA issue.
 // SYMK: Wh is a symmetric square matrix (c_out == c_in) and the epilogue forms a quadratic form in
-// it (EPI_DOT with Y == X): the tile with first output row o0 contracts only k >= o0, and its
-// first four k-tiles - the diagonal block - count half.  The caller doubles the result:
-// 2 * (sum_{k > block} + 1/2 sum_{k in block}) = the full contraction, at about half the flops.
+// it (EPI_DOT with Y == X): the tile with first output row o0 contracts only k >= o0, with the part
+// beyond its diagonal block counted twice: 2 * sum_{k > block} + sum_{k in block} stands for the
+// full contraction at about half the flops.  The k-tiles are walked from the END of the rows
+// down to o0, so that the tiles of a patch - which start at different o0 - work on the same
+// k-tile at the same time and share its token panel in L2; the diagonal block comes last.
 template <typename T, int NSTAGE, int EPI, bool SYMK = false>
 __global__ __launch_bounds__(512) void gemm_dma_kernel(GemmDev a) {
 #if defined(__HIP_DEVICE_COMPILE__)  // the body uses gfx950 builtins the host pass cannot parse
@@ -698,9 +700,11 @@ __global__ __launch_bounds__(512) void gemm_dma_kernel(GemmDev a) {
       __builtin_amdgcn_raw_ptr_buffer_load_lds(rB, (lds_ptr_t)(sbase + BO * RB + (j * NW + wave) * 1024), 16,
                                                live ? vob[j] : kOutOfRange, so, 0, 0);
   };
+  // byte offset of k-tile number kt of the walk inside a row
+  auto k_offset = [&](int64_t kt) { return (int)((SYMK ? nk - 1 - kt : kt) * BK_ * 2); };
   auto issue = [&](int64_t kt) {
     const bool live = kt < nk;
-    const int so = live ? (int)(kt * BK_ * 2) : 0;
+    const int so = live ? k_offset(kt) : 0;
     unsigned char* sb = lds + (int)(kt % NSTAGE) * STAGE;
     static_for<0, LPS>([&](auto dc) { dma1(dc, sb, live, so); });
   };
@@ -740,7 +744,7 @@ __global__ __launch_bounds__(512) void gemm_dma_kernel(GemmDev a) {
     constexpr int NR = 4 + (RDB ? 4 : 0);
     static_assert(NR + ND <= 16, "two side operations behind each of the first eight MFMAs");
     const bool live = dkt < nk;
-    const int so = live ? (int)(dkt * BK_ * 2) : 0;
+    const int so = live ? k_offset(dkt) : 0;
     unsigned char* sbase = lds + (int)(dkt % NSTAGE) * STAGE;
     // side operation number n of the phase: in the refill phase the LDS-DMA loads come first (the
     // longest latency), then the fragment reads
@@ -778,15 +782,7 @@ __global__ __launch_bounds__(512) void gemm_dma_kernel(GemmDev a) {
     lds_read128<m * 16 * RB>(Fb[0][m], offB[0]);
   });
   lds_wait8(Fa[0][0], Fa[0][1], Fa[0][2], Fa[0][3], Fb[0][0], Fb[0][1], Fb[0][2], Fb[0][3]);
-  constexpr int64_t kDiagTiles = BO / BK_;   // k-tiles of the diagonal block (SYMK)
-  auto halve = [&]() {
-#pragma unroll
-    for (int i = 0; i < IA; ++i)
-#pragma unroll
-      for (int j = 0; j < JB; ++j) acc[i][j] *= 0.5f;
-  };
-  for (int64_t kt = 0; kt < nk; ++kt) {
-    if (SYMK && kt == kDiagTiles) halve();
+  auto k_tile = [&](int64_t kt) {
     const uint32_t so_cur = (uint32_t)((kt % NSTAGE) * STAGE);
     phase(I0{}, I0{}, I0{}, I1{}, I0{}, I0{}, offA[0] + so_cur, 0u, 0);
     lds_wait4(Fa[1][0], Fa[1][1], Fa[1][2], Fa[1][3]);
@@ -802,10 +798,23 @@ __global__ __launch_bounds__(512) void gemm_dma_kernel(GemmDev a) {
     const uint32_t so_next = (uint32_t)(((kt + 1) % NSTAGE) * STAGE);
     phase(I1{}, I1{}, I1{}, I0{}, I1{}, I8{}, offA[0] + so_next, offB[0] + so_next, kt + NSTAGE);
     lds_wait8(Fa[0][0], Fa[0][1], Fa[0][2], Fa[0][3], Fb[0][0], Fb[0][1], Fb[0][2], Fb[0][3]);
+  };
+  int64_t kt = 0;
+  if constexpr (SYMK) {
+    // first everything beyond the diagonal block, counted twice; then the block itself
+    constexpr int64_t kDiagTiles = BO / BK_;
+    const int64_t n_beyond = nk > kDiagTiles ? nk - kDiagTiles : 0;
+    for (; kt < n_beyond; ++kt) k_tile(kt);
+    if (n_beyond > 0) {
+#pragma unroll
+      for (int i = 0; i < IA; ++i)
+#pragma unroll
+        for (int j = 0; j < JB; ++j) acc[i][j] *= 2.0f;
+    }
   }
+  for (; kt < nk; ++kt) k_tile(kt);
   wait_vmcnt<0>();
   __syncthreads();
-  if (SYMK && nk <= kDiagTiles) halve();
 
   // every LDS-DMA write has landed and every wave is past its last fragment read:
   // the tile memory is free for the per-token row sums and the Y_ref / output staging
@@ -869,21 +878,21 @@ static GemmDev make_dev(const GemmArgs& g) {
   return d;
 }
 
-// Whether launch_gemm_dot contracts only the upper part of a symmetric Wh (see SYMK): the caller
-// then has to double the partial sums.
-bool gemm_dot_symmetric(const GemmArgs& g) {
-  return g.sym_k && g.c_out == g.c_in && (g.c_in % kDmaBK) == 0 && g.ldw < (1 << 21) && g.ldx < (1 << 21);
+// Whether launch_gemm_dot contracts only the upper part of a symmetric Wh (see SYMK).
+// the pipelined kernel needs whole k-tiles and 32-bit byte offsets inside a 256-row panel
+static bool pipelined_ok(const GemmArgs& g) {
+  return (g.c_in % kDmaBK) == 0 && g.ldw < (1 << 21) && g.ldx < (1 << 21);
 }
+bool gemm_dot_symmetric(const GemmArgs& g) { return g.sym_k && g.c_out == g.c_in && pipelined_ok(g); }
 
 template <int EPI>
 static hipError_t launch_gemm(const GemmArgs& g, const char* name, hipStream_t stream) {
   GemmDev d = make_dev(g);
-  const int64_t rounds = ceil_div(d.n_patches, 8);
+  const int64_t rounds = ceil_div(d.n_patches, kXcd);
   const int64_t blocks = rounds * kXcd * PATCH_SLOTS;
   if (blocks > 0x7fffffffLL) return hipErrorInvalidValue;
-  // the pipelined kernel needs whole k-tiles and 32-bit byte offsets inside a 256-row panel
-  const bool dma = (g.c_in % kDmaBK) == 0 && g.ldw < (1 << 21) && g.ldx < (1 << 21);
-  const bool symk = EPI == EPI_DOT && dma && gemm_dot_symmetric(g);
+  const bool dma = pipelined_ok(g);
+  const bool symk = EPI == EPI_DOT && gemm_dot_symmetric(g);
   // (a symmetric product computes the tiles on and above the diagonal, a symmetric contraction
   // the k range from the diagonal block on: about half either way)
   const double tile_frac = (g.tri || symk) ? 0.5 * (1.0 + 1.0 / (double)d.tiles_o) : 1.0;

@@ -248,9 +248,9 @@ __global__ __launch_bounds__(1024) void finalize_kernel(
 
 hipError_t launch_finalize(const float* partial, int n_cand, int64_t tiles_per_cand, int64_t c_out,
                            const float* s_table, int64_t c_in, float* losses, int32_t* best_idx,
-                           float* best_scales, hipStream_t stream, const double* factor, double host_factor) {
+                           float* best_scales, hipStream_t stream, const double* factor) {
   ProfScope ps("finalize", stream, 4.0 * (double)n_cand * (double)tiles_per_cand);
-  finalize_kernel<<<1, 1024, 0, stream>>>(partial, n_cand, tiles_per_cand, host_factor / (double)c_out,
+  finalize_kernel<<<1, 1024, 0, stream>>>(partial, n_cand, tiles_per_cand, 1.0 / (double)c_out,
                                           factor, s_table, c_in, losses, best_idx, best_scales);
   return hipGetLastError();
 }
