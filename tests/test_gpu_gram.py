@@ -146,6 +146,24 @@ def test_gram_search_agrees_with_token_search(gpu):
         assert rel.max() < LOSS_RTOL, rel.max()
 
 
+def test_gram_search_correlated_channels(gpu):
+    """Activations dominated by one direction shared by all channels (x_t = 10 z_t a + noise), the
+    structure real decoder activations have: every entry of the balanced matrix is then of order
+    one and the quadratic form sums C_in^2 comparable terms."""
+    rng = np.random.default_rng(21)
+    n, ci, co = 3000, 512, 384
+    _, W, w = layer(9, n, ci, co)
+    a = rng.standard_normal(ci) * np.exp(rng.uniform(-2, 2, ci))
+    X = (10.0 * rng.standard_normal((n, 1)) * a[None, :] + rng.standard_normal((n, ci))).astype(np.float16)
+    alpha = wl.alpha_grid(20)
+    for bits in (4, 3):
+        p = tlq.params(bits=bits, group=128)
+        gram, xs, lg, bg, _, st = gram_search(X, W, w, p, gpu, False, alpha)
+        ref = orc.scale_search(X, W, orc.ref_output(X, W), w, bits, 128, alpha, x_stat=xs, s_table=st)
+        worst = check_losses(lg, ref["losses"], bg, f"correlated W{bits}")
+        print(f"W{bits}: max rel {worst:.2e}")
+
+
 def test_gram_degenerate_inputs(gpu):
     """All-zero token weights give zero losses and the first candidate; a dead channel (all-zero
     column of X) is harmless; one dominant token weight is handled by the max-normalisation."""
