@@ -156,14 +156,17 @@ def run_stack(h0, weights_fn, n_layers, token_w, alpha_grid, p, n_heads, seq_len
         if pb:
             prep = prepared_buffer(pb)
             tlq.prepare_tokens(Xq, p, prep)
-        gm = None
-        if gram:      # once per distinct exposed input as well
-            gb = tlq.token_gram_bytes(c_in)
-            if ws_cache.get("gn", 0) < gb:
-                ws_cache["g"] = None
-                ws_cache["g"] = torch.empty(gb, dtype=torch.uint8, device=dev)
-                ws_cache["gn"] = gb
-            gm = tlq.token_gram(Xq, token_w, p, ws_cache["g"][:gb], workspace=workspace(c_in, max(widths)))
+        gm = []
+
+        def group_gram():      # once per distinct exposed input as well, and only if a member is searched
+            if not gm:
+                gb = tlq.token_gram_bytes(c_in)
+                if ws_cache.get("gn", 0) < gb:
+                    ws_cache["g"] = None
+                    ws_cache["g"] = torch.empty(gb, dtype=torch.uint8, device=dev)
+                    ws_cache["gn"] = gb
+                gm.append(tlq.token_gram(Xq, token_w, p, ws_cache["g"][:gb], workspace=workspace(c_in, max(widths))))
+            return gm[0]
         units = [(names, torch.cat(Ws, dim=0) if len(Ws) > 1 else Ws[0], Y, Z)] if joint else \
                 [((n,), W, Yi, None if Z is None else Z[:, o:o + w]) for n, W, Yi, o, w in zip(names, Ws, Ys, offs, widths)]
         for unames, W, Yu, Zu in units:
@@ -181,7 +184,9 @@ def run_stack(h0, weights_fn, n_layers, token_w, alpha_grid, p, n_heads, seq_len
                 losses.copy_(torch.tensor(old["losses"], dtype=torch.float32))
             else:
                 if gram:
-                    tlq.scale_search_gram(gm, W, alpha_grid, p, xs_in, best, idx, losses, workspace=ws)
+                    g_in = group_gram()          # (may regrow the shared workspace: fetch `ws` after it)
+                    ws = workspace(c_in, W.shape[0])
+                    tlq.scale_search_gram(g_in, W, alpha_grid, p, xs_in, best, idx, losses, workspace=ws)
                 else:
                     tlq.scale_search(Xq, W, Yu, token_w, alpha_grid, p, best, idx, losses, x_stat_in=xs_in,
                                      workspace=ws, prepared=prep)

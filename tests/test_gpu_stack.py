@@ -109,12 +109,12 @@ def _mini(gpu):
     return sw, h0, Ws, w, al, tW
 
 
-def _gpu_run(gpu, sw, h0, tW, w, al, bits, mode, joint, journal=None, keep=True, n_layers=None):
+def _gpu_run(gpu, sw, h0, tW, w, al, bits, mode, joint, journal=None, keep=True, n_layers=None, strategy="tokens"):
     import torch
     p = tlq.params(bits=bits, group=sw.group, x_dtype=tlq.BF16, yref_dtype=tlq.BF16)
     return gstack.run_stack(dev(h0, gpu, True), lambda l: tW[l], n_layers or sw.n_layers,
                             torch.from_numpy(w).to(gpu), torch.from_numpy(al).to(gpu), p, sw.n_heads,
-                            sw.seq_len, mode=mode, joint=joint, journal=journal, keep=keep)
+                            sw.seq_len, mode=mode, joint=joint, journal=journal, keep=keep, strategy=strategy)
 
 
 # setting = (bits, group, symmetric, act_bits); the last one is the paper's own (W4 per-channel symmetric, A8)
@@ -255,11 +255,12 @@ def test_stack_gram_strategy(gpu, mode, joint):
                          strategy="gram")
 
 
-def test_stack_journal_resume(gpu, tmp_path):
+@pytest.mark.parametrize("strategy", ["tokens", "gram"])
+def test_stack_journal_resume(gpu, tmp_path, strategy):
     import torch
     sw, h0, Ws, w, al, tW = _mini(gpu)
     path = str(tmp_path / "journal.jsonl")
-    full, hq, _ = _gpu_run(gpu, sw, h0, tW, w, al, 3, "passact2", False, journal=gstack.Journal(path))
+    full, hq, _ = _gpu_run(gpu, sw, h0, tW, w, al, 3, "passact2", False, journal=gstack.Journal(path), strategy=strategy)
     lines = open(path).read().splitlines()
     assert len(lines) == 7 * sw.n_layers
     rec0 = json.loads(lines[0])
@@ -271,11 +272,16 @@ def test_stack_journal_resume(gpu, tmp_path):
     tlq.profile_enable(True)
     j = gstack.Journal(path)
     assert len(j.done) == 5
-    again, hq2, _ = _gpu_run(gpu, sw, h0, tW, w, al, 3, "passact2", False, journal=j)
+    again, hq2, _ = _gpu_run(gpu, sw, h0, tW, w, al, 3, "passact2", False, journal=j, strategy=strategy)
     torch.cuda.synchronize()
     tlq.profile_enable(False)
     launches = {k.name: k.launches for k in tlq.profile_read()}
-    assert launches.get("gemm_loss", 0) == 7 * sw.n_layers - 5        # finished searches are not repeated
+    if strategy == "tokens":
+        assert launches.get("gemm_loss", 0) == 7 * sw.n_layers - 5    # finished searches are not repeated
+    else:
+        assert launches.get("gemm_gram_loss", 0) == 7 * sw.n_layers - 5 and "gemm_loss" not in launches
+        # the groups q/k/v and o of the first block were finished: their matrices are not formed again
+        assert launches.get("gemm_gram", 0) == 4 * sw.n_layers - 2
     assert bool((hq == hq2).all())
     for a, b in zip(full, again):
         for n in ost.LINEARS:
