@@ -1,10 +1,10 @@
 """Turn two rocprofv3 counter runs of bench.py into profiles/traffic.json.
 
-    rocprofv3 --kernel-trace --pmc FETCH_SIZE --output-format csv -d gpurun_out/prof/fetch -o bench -- \\
+    rocprofv3 --kernel-trace --pmc FETCH_SIZE --output-format csv -d $OUT/fetch -o bench -- \\
         python3 bench.py --steps 1 --warmup 0 --no-cpu-baseline --no-ceiling
-    rocprofv3 --kernel-trace --pmc WRITE_SIZE --output-format csv -d gpurun_out/prof/write -o bench -- \\
+    rocprofv3 --kernel-trace --pmc WRITE_SIZE --output-format csv -d $OUT/write -o bench -- \\
         python3 bench.py --steps 1 --warmup 0 --no-cpu-baseline --no-ceiling
-    python -m paper_2602_07899_amd.record_traffic gpurun_out/prof
+    python -m paper_2602_07899_amd.record_traffic $OUT
 
 FETCH_SIZE / WRITE_SIZE count KiB crossing the L2 <-> fabric boundary per dispatch.  Each is
 scaled by what the same counter reads for bench.py's device-to-device calibration copy
@@ -83,4 +83,6 @@ def main(prof_dir):
 
 
 if __name__ == "__main__":
-    main(sys.argv[1] if len(sys.argv) > 1 else os.path.join(ROOT, "gpurun_out", "prof"))
+    if len(sys.argv) != 2:
+        sys.exit("usage: python -m paper_2602_07899_amd.record_traffic <directory holding fetch/ and write/>")
+    main(sys.argv[1])
