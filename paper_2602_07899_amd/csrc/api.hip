@@ -452,6 +452,7 @@ static tlq_status scale_search_impl(const void* X, int64_t n_tok, int64_t c_in, 
                                s.sig + (size_t)k0 * n_tok, s.rsig, st));
       GemmArgs b = g;
       b.X = s.xc; b.ldx = c_in; b.x_cand_stride = n_tok * c_in;
+      b.cand_outer = true;   // nothing is shared between candidates here: walk them one after the other
       b.tok_scale = s.sig + (size_t)k0 * n_tok;
       b.Wh = s.what + (size_t)k0 * c_out * c_in; b.n_cand = nb;
       b.partial = s.partial + (size_t)k0 * tiles;
