@@ -441,6 +441,9 @@ static tlq_status scale_search_impl(const void* X, int64_t n_tok, int64_t c_in, 
   if (diff) { g.Yref = s.d0; g.ldy = s.ldd; g.yref_dtype = TLQ_F32; }
   g.partial = s.partial; g.tok_partial = nullptr;
   if (!act) {
+    // patch shape by measurement: 8 x 4 tiles gain ~1 % on square and widening layers and lose
+    // 0.5 - 3 % on the narrowing, deep ones (down_proj)
+    g.wide_patch = c_in <= 2 * c_out;
     TLQ_HIP(launch_gemm_loss(g, st));
   } else {
     // Q_a(x / s_k) differs per candidate: quantise the tokens for a batch of candidates,
@@ -612,6 +615,7 @@ tlq_status tlq_ref_output(const void* X, int64_t n_tok, int64_t c_in, int64_t ld
   g.Wh = W; g.c_out = c_out; g.ldw = ldw; g.w_cand_stride = 0; g.n_cand = 1;
   g.bf16 = p->x_dtype == TLQ_BF16;
   g.Yout = Y; g.ldo = ldy; g.yout_dtype = p->yref_dtype;
+  g.wide_patch = true;   // one candidate: 8 weight panels stay per patch row, 4 token panels change (+1 .. +4 % measured)
   return hip_status(launch_gemm_store(g, (hipStream_t)stream));
 }
 
@@ -667,6 +671,7 @@ static tlq_status apply_best_impl(const void* X, int64_t n_tok, int64_t c_in, in
   g.tok_scale = sig;
   g.Wh = what; g.c_out = c_out; g.ldw = c_in; g.w_cand_stride = 0; g.n_cand = 1; g.bf16 = false;
   g.Yout = X_next; g.ldo = ld_next; g.yout_dtype = p->x_dtype;
+  g.wide_patch = true;   // one candidate: 8 weight panels stay per patch row, 4 token panels change (+1 .. +4 % measured)
   return hip_status(launch_gemm_store(g, st));
 }
 
