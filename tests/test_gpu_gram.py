@@ -91,6 +91,8 @@ CASES = [
     (640, 1024, 260, 3, 128, 0, True, "lognormal"),
     (500, 200, 130, 4, 40, 0, False, "lognormal"),
     (450, 320, 200, 4, 0, 1, False, "lognormal"),
+    (600, 256, 192, 8, 128, 0, False, "lognormal"),
+    (800, 384, 256, 6, 0, 1, True, "lognormal"),
     (37, 128, 64, 2, 64, 0, False, "lognormal"),
     (1, 64, 8, 4, 64, 0, False, "uniform"),
 ]
