@@ -148,6 +148,31 @@ def test_gram_search_agrees_with_token_search(gpu):
         assert rel.max() < LOSS_RTOL, rel.max()
 
 
+def test_gram_wide_layer_with_ragged_tile_row(gpu):
+    """C_in = 8512 = 33 tile rows + 64 channels: the token product runs with 8 x 4 patches and four
+    splits, the quadratic form's last tile row holds only part of a diagonal block.  Sampled entries
+    of the matrix and the search over 48 output rows against the oracle."""
+    rng = np.random.default_rng(33)
+    n, ci, co = 20000, 8512, 48
+    X, W, w = layer(31, n, ci, co)
+    alpha = wl.alpha_grid(20)
+    p = tlq.params(bits=4, group=64)
+    gram, xs, lg, bg, _, st = gram_search(X, W, w, p, gpu, False, alpha)
+    ri = np.sort(np.concatenate([rng.choice(ci, 20, replace=False), [0, 255, 256, 8447, 8448, 8511]]))
+    rj = np.sort(np.concatenate([rng.choice(ci, 20, replace=False), [1, 8191, 8192, 8450, 8511]]))
+    f, cs, C = tlq.gram_views(gram, ci)
+    import torch
+    csn = cs.double().cpu().numpy()
+    Cs = C[torch.from_numpy(ri).to(gpu)][:, torch.from_numpy(rj).to(gpu)].double().cpu().numpy()
+    G = float(f.item()) * csn[ri][:, None] * csn[rj][None, :] * Cs
+    Go = orc.token_second_moment(X, w, rows=ri, cols=rj)
+    dg = np.sqrt(float(f.item()) * csn ** 2 * torch.diagonal(C).double().cpu().numpy())
+    assert np.all(np.abs(G - Go) <= 2.0 ** -9 * dg[ri][:, None] * dg[rj][None, :])
+    ref = orc.scale_search(X, W, orc.ref_output(X, W), w, 4, 64, alpha, x_stat=xs, s_table=st)
+    worst = check_losses(lg, ref["losses"], bg, "wide layer")
+    print(f"max rel {worst:.2e}, best {bg}")
+
+
 def test_gram_search_correlated_channels(gpu):
     """Activations dominated by one direction shared by all channels (x_t = 10 z_t a + noise), the
     structure real decoder activations have: every entry of the balanced matrix is then of order
