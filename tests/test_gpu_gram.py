@@ -173,6 +173,33 @@ def test_gram_wide_layer_with_ragged_tile_row(gpu):
     print(f"max rel {worst:.2e}, best {bg}")
 
 
+def test_gram_strided_operands(gpu):
+    """X and W as column slices of wider matrices (row strides larger than C_in): same bits as the
+    dense call."""
+    import torch
+    X, W, w = layer(12, 700, 384, 200)
+    p = tlq.params(bits=4, group=128)
+    alpha = wl.alpha_grid(20)
+    gram0, xs0, l0, b0, _, _ = gram_search(X, W, w, p, gpu, False, alpha)
+    Xw = torch.full((700, 512), 7.0, dtype=torch.float16, device=gpu)
+    Ww = torch.full((200, 448), -3.0, dtype=torch.float16, device=gpu)
+    Xw[:, 64:448] = dev(X, gpu)
+    Ww[:, 32:416] = dev(W, gpu)
+    Xs, Wsl = Xw[:, 64:448], Ww[:, 32:416]
+    assert Xs.stride(0) == 512 and Wsl.stride(0) == 448
+    xs = torch.empty(384, dtype=torch.float32, device=gpu)
+    tlq.x_stat(Xs, p, xs)
+    gram = torch.empty(tlq.token_gram_bytes(384), dtype=torch.uint8, device=gpu)
+    tlq.token_gram(Xs, dev(w, gpu), p, gram)
+    out = (torch.empty(384, dtype=torch.float32, device=gpu), torch.empty(1, dtype=torch.int32, device=gpu),
+           torch.empty(20, dtype=torch.float32, device=gpu))
+    tlq.scale_search_gram(gram, Wsl, dev(alpha, gpu), p, xs, *out)
+    torch.cuda.synchronize()
+    for a, b in zip(tlq.gram_views(gram, 384), tlq.gram_views(gram0, 384)):      # (padding bytes are not written)
+        assert torch.equal(a, b)
+    assert np.array_equal(out[2].cpu().numpy(), l0) and int(out[1].item()) == b0
+
+
 def test_gram_search_correlated_channels(gpu):
     """Activations dominated by one direction shared by all channels (x_t = 10 z_t a + noise), the
     structure real decoder activations have: every entry of the balanced matrix is then of order
