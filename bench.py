@@ -264,6 +264,26 @@ def oracle_leg(wl, tlq, torch, orc, workload, dev, p, n_samples, cands, x_abs_su
     return base, parity
 
 
+def stack_leg(torch, n_blocks=2):
+    """Config 5 in short: the first `n_blocks` decoder blocks of the 13B-class stack (bf16 activations,
+    W4 g128, PassAct2, 153,600 tokens, 7 linears x 20 alphas per block) calibrated sequentially
+    by the stack driver, once per search form.  The 40 blocks of the full stack have identical
+    shapes, so the 40-block figure is the per-block time x 40 (labelled as extrapolated; the
+    full runs are in profiles/stack_cfg5_13b.md)."""
+    from paper_2602_07899_amd import run_stack
+    out = {"stack": "cfg5_13b_stack", "bits": 4, "blocks_run": n_blocks, "extrapolated_to_blocks": 40}
+    for strategy in ("tokens", "gram"):
+        r = run_stack.run("cfg5_13b_stack", 4, mode="passact2", n_layers=n_blocks, strategy=strategy,
+                          log=lambda m: log(m.replace("[run_stack] ", "stack: ")))
+        out[strategy] = {"wall_s": r["wall_s"], "s_per_block": r["wall_s"] / n_blocks,
+                         "wall_s_40_blocks_extrapolated": r["wall_s"] / n_blocks * 40,
+                         "search_kernels_s": r["search_kernels_s"], "propagate_kernels_s": r["propagate_kernels_s"],
+                         "block_kernels_s": r["block_kernels_s"], "h_finite": r["h_finite"],
+                         "best_idx_first_block": r["blocks"][0]["best_idx"]}
+        torch.cuda.empty_cache()
+    return out
+
+
 def mfma_ceiling():
     """Context for the roofline fraction: what a register-only fp16 MFMA loop
     sustains on this device with constant and with pseudo-random operands."""
@@ -292,6 +312,8 @@ def main():
     ap.add_argument("--no-cpu-baseline", action="store_true", help="skip the oracle timing and parity legs")
     ap.add_argument("--no-second-moment", action="store_true",
                     help="skip the second-moment-form leg (the same searches through the token Gram matrix)")
+    ap.add_argument("--no-stack", action="store_true",
+                    help="skip the short sequential-stack leg (two blocks of the 13B-class stack per search form)")
     ap.add_argument("--no-ceiling", action="store_true",
                     help="skip the register-only MFMA ceiling measurement (context only)")
     args = ap.parse_args()
@@ -361,6 +383,8 @@ def main():
         sec = run(other)
         sec["unit"] = "evals/s"
         result["secondary"] = sec
+    if args.act_bits == 0 and not args.no_stack:
+        result["stack"] = stack_leg(torch)
     result["peak_hbm_bytes"] = int(torch.cuda.max_memory_allocated())
     result["source_fingerprint"] = source_fingerprint()
     # the paper publishes no speed figure for this path; its cost figures are about memory
