@@ -128,7 +128,7 @@ def run(stack_name, bits, mode="passact2", joint=False, n_layers=None, n_samples
     block_ms = sum(k.total_ms for n, k in prof.items() if n in BLOCK_KERNELS)
     prop_ms = sum(k.total_ms for n, k in prof.items()
                   if n not in SEARCH_KERNELS and n not in BLOCK_KERNELS and n not in SELECT_KERNELS)
-    gl = prof.get("gemm_gram_loss" if strategy == "gram" else "gemm_loss")
+    gl = prof.get("gemm_loss") or prof.get("gemm_gram_loss")
     out = {
         "stack": stack_name, "bits": bits, "group": p.group, "symmetric": bool(p.symmetric), "mode": mode,
         "joint": joint, "act_bits": act_bits, "x_stat": xstat, "strategy": strategy, "layers": layers,
@@ -163,9 +163,10 @@ def main():
     ap.add_argument("--symmetric", action="store_true")
     ap.add_argument("--xstat", default="mean", choices=("mean", "topk"),
                     help="mean |x| (default) or the maximum over the Top-50%% positions by synthetic gradient norm")
-    ap.add_argument("--strategy", default="tokens", choices=("tokens", "gram"),
+    ap.add_argument("--strategy", default="tokens", choices=("tokens", "gram", "auto"),
                     help="tokens: every candidate contracts the tokens; gram: candidates are evaluated through the "
-                         "weighted second-moment matrix of the exposed input (weight-only, not passact1)")
+                         "weighted second-moment matrix of the exposed input (weight-only, not passact1); auto: per "
+                         "group of linears, whichever the flop model favours")
     ap.add_argument("--journal", default=None)
     ap.add_argument("--brief", action="store_true", help="leave the per-block records out of the summary")
     a = ap.parse_args()

@@ -86,6 +86,18 @@ class Journal:
                 os.fsync(f.fileno())
 
 
+def second_moment_pays(n_tok, c_in, widths, n_alpha):
+    """Flop model behind strategy="auto": contracting the tokens with every candidate costs
+    2 N C_in C_out per candidate; the second-moment form N C_in^2 once per group (symmetric
+    product) plus C_out C_in^2 per candidate (symmetric contraction).  Its contractions run at
+    about three quarters of the token form's rate (short launches, tiles of unequal length), so it is
+    chosen when its flop count is under half of the token form's."""
+    c_out = sum(widths)
+    tokens = 2.0 * n_alpha * n_tok * c_in * c_out
+    moment = float(n_tok) * c_in * c_in + float(n_alpha) * c_out * c_in * c_in
+    return moment < 0.5 * tokens
+
+
 def run_stack(h0, weights_fn, n_layers, token_w, alpha_grid, p, n_heads, seq_len, mode="passact2",
               joint=False, journal=None, keep=False, on_layer=None, xstat_fn=None, strategy="tokens"):
     """h0 [n_tok, n_heads*128] device tensor in the activation type; weights_fn(layer)
@@ -99,12 +111,14 @@ def run_stack(h0, weights_fn, n_layers, token_w, alpha_grid, p, n_heads, seq_len
     statistic p.xstat_kind names.  strategy "gram" evaluates the candidates through the weighted
     second-moment matrix of each group's exposed input (tlq.token_gram / scale_search_gram): weight-only
     settings whose target is f_fp of that same input, i.e. not PassAct1; the target then is the exact
-    product and, under PassAct2, the full-precision outputs are not formed at all."""
+    product and, under PassAct2, the full-precision outputs are not formed at all.  strategy "auto"
+    decides per group of linears with `second_moment_pays`."""
     import torch
     assert mode in ("none", "passact1", "passact2")
-    assert strategy in ("tokens", "gram")
-    gram = strategy == "gram"
-    assert not gram or (mode != "passact1" and p.act_bits == 0), "the second-moment form needs f_q linear in the searched input"
+    assert strategy in ("tokens", "gram", "auto")
+    gram_ok = mode != "passact1" and p.act_bits == 0
+    assert strategy != "gram" or gram_ok, "the second-moment form needs f_q linear in the searched input"
+    gram_any = strategy == "gram" or (strategy == "auto" and gram_ok)     # some group may use it
     dev, act = h0.device, h0.dtype
     n_tok, d = h0.shape
     assert d == n_heads * 128 and n_tok % seq_len == 0
@@ -116,9 +130,9 @@ def run_stack(h0, weights_fn, n_layers, token_w, alpha_grid, p, n_heads, seq_len
     ws_cache = {}
 
     def workspace(c_in, c_out):
-        need = max(tlq.scale_search_gram_workspace_bytes(c_in, c_out, na, p) if gram else
-                   tlq.scale_search_workspace_bytes(n_tok, c_in, c_out, na, p),
-                   tlq.token_gram_workspace_bytes(n_tok, c_in) if gram else 0,
+        need = max(tlq.scale_search_gram_workspace_bytes(c_in, c_out, na, p) if gram_any else 0,
+                   tlq.scale_search_workspace_bytes(n_tok, c_in, c_out, na, p) if strategy != "gram" else 0,
+                   tlq.token_gram_workspace_bytes(n_tok, c_in) if gram_any else 0,
                    tlq.apply_best_workspace_bytes(n_tok, c_in, c_out, p), tlq.x_stat_workspace_bytes(n_tok, c_in))
         if ws_cache.get("n", 0) < need:
             ws_cache["t"] = None
@@ -139,6 +153,7 @@ def run_stack(h0, weights_fn, n_layers, token_w, alpha_grid, p, n_heads, seq_len
         widths = [W.shape[0] for W in Ws]
         c_in, tot = Ws[0].shape[1], sum(widths)
         offs = [sum(widths[:i]) for i in range(len(Ws))]
+        gram = strategy == "gram" or (strategy == "auto" and gram_ok and second_moment_pays(n_tok, c_in, widths, na))
         need_y = not (gram and mode == "passact2")       # the target enters only through the matrix there
         Y = new(tot, y_dt) if need_y else None
         Ys = [Y[:, o:o + w] for o, w in zip(offs, widths)] if need_y else [None] * len(Ws)

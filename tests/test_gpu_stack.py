@@ -253,6 +253,12 @@ def test_stack_gram_strategy(gpu, mode, joint):
     with pytest.raises(AssertionError):
         gstack.run_stack(dev(h0, gpu, True), lambda l: tW[l], 1, tw, tal, pg, sw.n_heads, sw.seq_len, mode="passact1",
                          strategy="gram")
+    # "auto" on this small stack (fewer tokens than the flop model asks for) is the token form, bit for bit
+    outa, hqa, _ = run("auto")
+    assert bool((hqa == hqt).all())
+    for a, t in zip(outa, outt):
+        for n in ost.LINEARS:
+            assert bool((a[n]["losses"] == t[n]["losses"]).all())
 
 
 @pytest.mark.parametrize("strategy", ["tokens", "gram"])
